@@ -1,0 +1,183 @@
+"""Python face of the CPU oracle (oracle/serveflow_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product package never imports this module and
+this module never imports the product package.
+
+Every function takes and returns numpy arrays; see the C file for what each step
+computes and which passage of the paper it follows.
+"""
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "serveflow_oracle.c")
+_LIB = os.path.join(_HERE, "libsf_oracle.so")
+
+CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+          "-fno-unsafe-math-optimizations", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (one second); returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_vmin_from_theta.restype = ctypes.c_uint32
+        _lib.oracle_vmin_from_theta.argtypes = [ctypes.c_float, ctypes.c_uint32]
+        _lib.oracle_route.restype = ctypes.c_uint32
+        for name in ("oracle_featurize", "oracle_fast_infer", "oracle_slow_infer",
+                     "oracle_universal_thresholds", "oracle_max_window"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def default_threads() -> int:
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def featurize(flow_off, pkt_size, pkt_iat, pkt_dir, depths: Sequence[int], pkt_hdr=None,
+              raw_pkts: int = 0, raw_bits: int = 0, feat_ld: Optional[int] = None,
+              want_raw: bool = False, n_threads: int = 1) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    lib = _load()
+    flow_off = _c(flow_off, np.uint32)
+    pkt_size, pkt_iat, pkt_dir = _c(pkt_size, np.uint16), _c(pkt_iat, np.float32), _c(pkt_dir, np.uint8)
+    n = flow_off.shape[0] - 1
+    W = len(depths)
+    ld = 32 * W if feat_ld is None else feat_ld
+    feat = np.zeros((n, ld), dtype=np.float32)
+    dep = np.asarray(list(depths), dtype=np.uint32)
+    hdr_words = 0
+    raw = None
+    if pkt_hdr is not None:
+        pkt_hdr = _c(pkt_hdr, np.uint32)
+        hdr_words = pkt_hdr.shape[1]
+    if want_raw:
+        raw = np.zeros((n, raw_pkts * raw_bits), dtype=np.uint8)
+    rc = lib.oracle_featurize(ctypes.c_uint32(n), _p(flow_off), _p(pkt_size), _p(pkt_iat), _p(pkt_dir),
+                              _p(pkt_hdr), ctypes.c_uint32(hdr_words), ctypes.c_uint32(W), _p(dep),
+                              ctypes.c_uint32(raw_pkts), ctypes.c_uint32(raw_bits), _p(feat),
+                              ctypes.c_uint32(ld), _p(raw), ctypes.c_int(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_featurize: invalid arguments")
+    return feat, raw
+
+
+def fast_infer(feat, forest, want_votes: bool = True, want_leaves: bool = False, n_threads: int = 1):
+    """forest: any object with n_trees, depth, n_classes, n_features, node_feat, node_thr, leaf_label."""
+    lib = _load()
+    feat = _c(feat, np.float32)
+    n, ld = feat.shape
+    T, C = forest.n_trees, forest.n_classes
+    nf, nt, ll = _c(forest.node_feat, np.uint16), _c(forest.node_thr, np.float32), _c(forest.leaf_label, np.uint8)
+    votes = np.zeros((n, C), np.uint16) if want_votes else None
+    leaves = np.zeros((n, T), np.uint16) if want_leaves else None
+    pred = np.zeros(n, np.uint16)
+    top = np.zeros(n, np.uint16)
+    rc = lib.oracle_fast_infer(ctypes.c_uint32(n), _p(feat), ctypes.c_uint32(ld), ctypes.c_uint32(T),
+                               ctypes.c_uint32(forest.depth), ctypes.c_uint32(C),
+                               ctypes.c_uint32(forest.n_features), _p(nf), _p(nt), _p(ll),
+                               _p(votes), _p(pred), _p(top), _p(leaves), ctypes.c_int(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_fast_infer: invalid arguments")
+    return votes, pred, top, leaves
+
+
+def vmin_from_theta(theta: float, n_trees: int) -> int:
+    return int(_load().oracle_vmin_from_theta(ctypes.c_float(np.float32(theta)), ctypes.c_uint32(n_trees)))
+
+
+def route(top_votes, pred, vmin) -> np.ndarray:
+    lib = _load()
+    top_votes, pred = _c(top_votes, np.uint16), _c(pred, np.uint16)
+    vm = _c(np.atleast_1d(vmin), np.uint16)
+    n = top_votes.shape[0]
+    esc = np.zeros(max(n, 1), np.uint32)
+    cnt = lib.oracle_route(ctypes.c_uint32(n), _p(top_votes), _p(pred), _p(vm),
+                           ctypes.c_uint32(vm.shape[0]), _p(esc))
+    return esc[:cnt].copy()
+
+
+def universal_thresholds(scores, quantiles) -> np.ndarray:
+    lib = _load()
+    s, q = _c(scores, np.float64), _c(quantiles, np.float64)
+    out = np.zeros(q.shape[0], np.float64)
+    rc = lib.oracle_universal_thresholds(_p(s), ctypes.c_uint32(s.shape[0]), _p(q),
+                                         ctypes.c_uint32(q.shape[0]), _p(out))
+    if rc != 0:
+        raise ValueError("oracle_universal_thresholds: empty score list")
+    return out
+
+
+def slow_infer(esc_idx, mlp, n_flows: int, feat=None, flow_off=None, pkt_hdr=None, raw_pkts: int = 0,
+               raw_bits: int = 0, labels: Optional[np.ndarray] = None, n_threads: int = 1):
+    """mlp: any object with dims, dtype, w1..b3, mu, inv_sigma, clamp.  Returns (logits, labels);
+    ``labels`` (length n_flows) is updated at escalated positions only."""
+    lib = _load()
+    esc_idx = _c(esc_idx, np.uint32)
+    E = esc_idx.shape[0]
+    n_in, h1, h2, C = mlp.dims
+    logits = np.zeros((E, C), np.float32)
+    if labels is None:
+        labels = np.zeros(n_flows, np.uint16)
+    assert labels.dtype == np.uint16 and labels.flags.c_contiguous and labels.shape[0] == n_flows
+    ld = hdr_words = 0
+    if feat is not None:
+        feat = _c(feat, np.float32)
+        ld = feat.shape[1]
+    else:
+        flow_off, pkt_hdr = _c(flow_off, np.uint32), _c(pkt_hdr, np.uint32)
+        hdr_words = pkt_hdr.shape[1]
+    w = [_c(getattr(mlp, k), np.float32) for k in ("w1", "b1", "w2", "b2", "w3", "b3")]
+    mu = None if mlp.mu is None else _c(mlp.mu, np.float32)
+    isg = None if mlp.inv_sigma is None else _c(mlp.inv_sigma, np.float32)
+    rc = lib.oracle_slow_infer(ctypes.c_uint32(E), _p(esc_idx), _p(feat), ctypes.c_uint32(ld),
+                               _p(flow_off), _p(pkt_hdr), ctypes.c_uint32(hdr_words),
+                               ctypes.c_uint32(raw_pkts), ctypes.c_uint32(raw_bits),
+                               ctypes.c_uint32(n_in), ctypes.c_uint32(h1), ctypes.c_uint32(h2),
+                               ctypes.c_uint32(C), ctypes.c_int(1 if mlp.dtype == "bf16" else 0),
+                               _p(mu), _p(isg), ctypes.c_float(mlp.clamp),
+                               *[_p(a) for a in w], _p(logits), _p(labels), ctypes.c_int(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_slow_infer: invalid arguments")
+    return logits, labels
+
+
+def classify(pk, depths, forest, vmin, mlp, raw_pkts=0, raw_bits=0, n_threads: int = 1):
+    """All five steps in order; returns a dict of every intermediate result."""
+    feat, _ = featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, depths, n_threads=n_threads)
+    votes, pred, top, leaves = fast_infer(feat, forest, want_leaves=True, n_threads=n_threads)
+    esc = route(top, pred, vmin)
+    labels = pred.copy()
+    if raw_pkts:
+        logits, labels = slow_infer(esc, mlp, feat.shape[0], flow_off=pk.flow_off, pkt_hdr=pk.pkt_hdr,
+                                    raw_pkts=raw_pkts, raw_bits=raw_bits, labels=labels,
+                                    n_threads=n_threads)
+    else:
+        logits, labels = slow_infer(esc, mlp, feat.shape[0], feat=feat, labels=labels,
+                                    n_threads=n_threads)
+    return dict(feat=feat, votes=votes, pred=pred, top_votes=top, leaf_idx=leaves, esc_idx=esc,
+                logits=logits, labels=labels)
