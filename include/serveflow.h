@@ -1,0 +1,193 @@
+/*
+ * serveflow.h - C ABI of the batched fast-slow flow classifier for AMD MI355X (gfx950).
+ *
+ * The library runs the data-parallel hot path of a fast-slow model architecture for
+ * network traffic analysis (Section 3.1 of the paper): every flow is featurised from its
+ * first k packets and classified by a fast tree ensemble; an uncertainty score decides
+ * which flows are certain enough (Section 3.2); the uncertain ones are compacted into a
+ * list and re-classified by a slower dense model, whose label replaces the fast one.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers inside the structs and pointer arguments are DEVICE pointers unless the
+ *     name starts with host_.  The structs themselves live in host memory.
+ *   - The caller owns every buffer.  The library owns only the sf_ctx object.  No entry
+ *     point allocates or frees device memory; scratch comes from the workspace handed to
+ *     sf_create.
+ *   - Work is enqueued on the context's HIP stream and the call returns without waiting;
+ *     outputs are valid once the caller has synchronised that stream.  (sf_validate_* are
+ *     the exception: they wait and report.)
+ *   - Every call returns an int status (SF_OK = 0, negative = error), never throws and
+ *     never aborts.  Argument errors that the host can see return SF_EINVAL before
+ *     anything is launched; sf_last_error() then describes the problem.
+ *   - Kernels clamp offsets and indices read from device memory into range, so malformed
+ *     device data gives wrong answers, not memory faults; sf_validate_* finds such data.
+ *   - Calls on one context must not overlap (one stream, one workspace).
+ */
+#ifndef SERVEFLOW_H
+#define SERVEFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sf_ctx sf_ctx;
+
+enum {
+    SF_OK = 0,
+    SF_EINVAL = -1,       /* bad argument (null pointer, size out of range, bad layout)   */
+    SF_ENOMEM = -2,       /* workspace too small for this call                           */
+    SF_EHIP = -3,         /* a HIP runtime call failed; see sf_last_error                */
+    SF_EUNSUPPORTED = -4, /* a size beyond the compiled limits                           */
+    SF_EDATA = -5         /* sf_validate_*: device data violates the documented layout   */
+};
+
+enum { SF_F32 = 0, SF_BF16 = 1 };
+
+/* compiled limits */
+#define SF_MAX_WINDOWS 4     /* prefix windows per flow                                  */
+#define SF_MAX_DEPTH_PKTS 64 /* packets of a flow the feature step looks at              */
+#define SF_MAX_FEATURES 128  /* 32 * SF_MAX_WINDOWS                                      */
+#define SF_MAX_TREE_DEPTH 14
+#define SF_MAX_CLASSES 64
+#define SF_HDR_WORDS_MAX 32  /* 1024 header bits per packet                              */
+
+/* ---- context ------------------------------------------------------------------------ */
+
+/* Scratch bytes that cover every entry point for at most max_flows flows per call, a
+ * forest of n_trees trees of depth tree_depth and an MLP with hidden widths n_h1, n_h2
+ * (pass zeros for the parts not used).  Host function, no GPU needed. */
+size_t sf_workspace_bytes(uint32_t max_flows, uint32_t n_trees, uint32_t tree_depth,
+                          uint32_t n_h1, uint32_t n_h2);
+
+/* Create a context bound to hip_stream (a hipStream_t; NULL = the default stream) and to
+ * a caller-owned device workspace of workspace_bytes bytes (256-byte aligned).  The
+ * workspace must stay valid until sf_destroy.  Needs a GPU. */
+int sf_create(sf_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes);
+void sf_destroy(sf_ctx* ctx);
+/* Text of the last error on this context (or of the last failed sf_create when ctx is
+ * NULL).  The string belongs to the library; it stays valid until the next call. */
+const char* sf_last_error(const sf_ctx* ctx);
+
+/* ---- step 1: features from the first k packets ---------------------------------------
+ * Section 3.1: the amount of context (first k packets) is the key parameter; packet sizes,
+ * inter-arrival times and direction are the flow-level inputs; Section 4.1: the raw header
+ * bits of each packet are the alternative representation.
+ *
+ * Packet records are SoA, grouped by flow (CSR): flow i owns packets
+ * [flow_off[i], flow_off[i+1]).  For window w the first m = min(n_i, depth[w]) packets are
+ * summarised as 32 floats: for group g in (dir==0, dir==1, all) and quantity q in (size,
+ * inter-arrival time) the five statistics mean, population std, min, max, median, at column
+ * 32*w + 10*g + 5*q + s; column 32*w+30 = total bytes, 32*w+31 = m.  An empty group gives
+ * zeros.  All arithmetic is binary32, one rounding per operation, sums in packet order,
+ * variance by the two-pass formula. */
+typedef struct {
+    uint32_t n_flows;
+    uint64_t n_pkts;
+    const uint32_t* flow_off; /* [n_flows+1], flow_off[0] = 0, non-decreasing, last = n_pkts */
+    const uint16_t* pkt_size; /* [n_pkts] bytes                                              */
+    const float* pkt_iat;     /* [n_pkts] seconds, finite                                    */
+    const uint8_t* pkt_dir;   /* [n_pkts] 0 or 1                                             */
+    const uint32_t* pkt_hdr;  /* optional [n_pkts][hdr_words]: header byte k is bits
+                                 8*(k%4)..8*(k%4)+7 of word k/4; header bit b is bit 7-(b%8)
+                                 of byte b/8.  May be NULL.                                   */
+    uint32_t hdr_words;       /* words per packet in pkt_hdr (15 for 480 bits), 0 if NULL     */
+} sf_packets;
+
+typedef struct {
+    uint32_t n_windows;               /* 1..SF_MAX_WINDOWS                                  */
+    uint32_t depth[SF_MAX_WINDOWS];   /* strictly increasing, 1..SF_MAX_DEPTH_PKTS          */
+    uint32_t raw_pkts, raw_bits;      /* raw header-bit features: first raw_pkts packets x
+                                         raw_bits bits each (0,0 = none)                    */
+} sf_feat_cfg;
+
+/* feat: [n_flows][feat_ld] float, feat_ld >= 32*n_windows; columns beyond 32*n_windows are
+ * left untouched.  raw: optional [n_flows][raw_pkts*raw_bits] bytes in {0,1} (feature
+ * raw_bits*j + b = header bit b of packet j, zeros past the end of the flow); NULL skips it.
+ * n_flows = 0 is a successful no-op. */
+int sf_featurize(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, float* feat,
+                 uint32_t feat_ld, uint8_t* raw);
+
+/* Waits for the stream, then checks the CSR layout on the device: flow_off[0] = 0,
+ * non-decreasing, last = n_pkts, pkt_dir in {0,1}, pkt_iat finite.  SF_EDATA if violated. */
+int sf_validate_packets(sf_ctx* ctx, const sf_packets* pk);
+
+/* ---- steps 2-3: fast model on every flow, uncertainty score ---------------------------
+ * Section 3.1: the fast model sees all traffic.  Section 3.2: least confidence
+ * LC(x) = 1 - max_y P(y|x).  The fast model here is a hard-voting ensemble of perfect
+ * binary trees; with P(y|x) = votes[y] / n_trees the score is carried exactly by the
+ * integer top_votes = max_y votes[y] (LC = 1 - top_votes / n_trees).
+ *
+ * Trees are stored in heap order: node k of tree t tests x[node_feat[t][k]] <= node_thr[t][k];
+ * true goes to 2k+1, false to 2k+2; after depth steps the leaf is k - (2^depth - 1) and the
+ * tree votes leaf_label[t][leaf].  pred = the class with most votes, lowest index on ties. */
+typedef struct {
+    uint32_t n_trees, depth, n_classes, n_features; /* depth 1..SF_MAX_TREE_DEPTH           */
+    const uint16_t* node_feat; /* [n_trees][2^depth - 1], values < n_features               */
+    const float* node_thr;     /* [n_trees][2^depth - 1]                                    */
+    const uint8_t* leaf_label; /* [n_trees][2^depth], values < n_classes                    */
+} sf_forest;
+
+/* feat: [n_flows][feat_ld], n_features <= feat_ld.  pred, top_votes: [n_flows].
+ * votes: optional [n_flows][n_classes]; leaf_idx: optional [n_flows][n_trees] (for parity
+ * checks).  Uses workspace for a packed copy of the forest (8 bytes per node). */
+int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
+                  const sf_forest* forest, uint16_t* votes, uint16_t* pred,
+                  uint16_t* top_votes, uint16_t* leaf_idx);
+
+/* Waits, then checks node_feat < n_features and leaf_label < n_classes on the device. */
+int sf_validate_forest(sf_ctx* ctx, const sf_forest* forest);
+
+/* ---- step 4: the gate ------------------------------------------------------------------
+ * Section 3.2: flows whose uncertainty exceeds a threshold are assigned to the slower model.
+ * In integers: flow i escalates iff top_votes[i] < vmin, with vmin = ceil(theta * n_trees)
+ * for "vote fraction below theta" (sf_vmin_from_theta forms it exactly).  host_vmin holds
+ * one threshold (n_vmin = 1, universal) or one per class (n_vmin = number of classes,
+ * threshold = host_vmin[pred[i]]; pred values >= n_vmin use the last entry).
+ * esc_idx receives the escalated flow indices in ascending order (capacity n_flows),
+ * *esc_count their number; both stay on the device. */
+int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
+             const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx,
+             uint32_t* esc_count);
+
+/* ceil(theta * n_trees), exact for theta's binary32 value, clamped to 0..65535.  Host. */
+uint32_t sf_vmin_from_theta(float theta, uint32_t n_trees);
+
+/* ---- step 5: slow model on the escalated flows only ------------------------------------
+ * Sections 3.1 and 4.4: only flows the fast model is unsure of reach the slow model, and
+ * its answer replaces the fast one.  The slow model is a 3-layer ReLU MLP.
+ *
+ * Input row of escalated flow i: feat[i][0..n_in) mapped by
+ * z = clamp((x - mu) * inv_sigma, -clamp, +clamp) in binary32 (identity if mu is NULL), or,
+ * when raw_src is given, the n_in = raw_pkts*raw_bits header bits of the flow read straight
+ * from the packed words ({0,1}, no map).  dtype SF_BF16: z is rounded to bfloat16, the
+ * weights are bfloat16, products accumulate in binary32 on the matrix cores and hidden
+ * activations are rounded to bfloat16 between layers.  dtype SF_F32: all binary32.
+ * label = arg-max of the logits, lowest index on ties. */
+typedef struct {
+    uint32_t n_in, n_h1, n_h2, n_classes;
+    int dtype;                        /* SF_F32 or SF_BF16                                   */
+    const float* mu;                  /* [n_in] or NULL                                      */
+    const float* inv_sigma;           /* [n_in] or NULL (both or neither)                    */
+    float clamp;
+    const void *w1, *w2, *w3;         /* row-major [out][in]; float or bfloat16 (uint16 bit
+                                         patterns) according to dtype                        */
+    const float *b1, *b2, *b3;        /* [out]                                               */
+} sf_mlp;
+
+/* esc_idx / esc_count: as written by sf_route (device).  At most esc_cap flows are
+ * processed (the capacity of logits; pass n_flows to process all).  logits: optional
+ * [esc_cap][n_classes].  labels: [n_flows], in/out: the caller pre-fills it with the fast
+ * prediction; entries of escalated flows are overwritten with the slow label.
+ * Exactly one of feat / raw_src is given.  Uses workspace for hidden activations. */
+int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_packets* raw_src,
+                  const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx,
+                  const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_flows,
+                  const sf_mlp* mlp, float* logits, uint16_t* labels);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SERVEFLOW_H */

@@ -1,0 +1,13 @@
+"""Batched fast-slow flow classification on AMD MI355X (gfx950).
+
+The product is the HIP library libserveflow_hip.so (C ABI in include/serveflow.h); this
+package is its thin Python binding.  Build the library with ``python -m
+paper_2402_03694_amd.build``; importing ``binding`` without it fails loudly (there is no
+CPU fallback).
+"""
+from .binding import (SF_BF16, SF_F32, DeviceForest, DeviceMlp, DevicePackets, ServeFlow, ServeFlowError,
+                      sf_vmin_from_theta, sf_workspace_bytes)
+from .upload import forest_to_device, mlp_to_device, packets_to_device
+
+__all__ = ["SF_BF16", "SF_F32", "DeviceForest", "DeviceMlp", "DevicePackets", "ServeFlow", "ServeFlowError",
+           "sf_vmin_from_theta", "sf_workspace_bytes", "forest_to_device", "mlp_to_device", "packets_to_device"]

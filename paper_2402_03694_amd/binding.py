@@ -1,0 +1,272 @@
+"""ctypes binding of libserveflow_hip.so: argument marshalling only.
+
+Every step of the path (featurize, fast model, gate, slow model) runs in the library's HIP
+kernels; this module turns torch device tensors into the pointers and sizes of the C ABI
+declared in include/serveflow.h.  torch is used for device memory and the stream, nothing
+else.  There is no CPU fallback: if the library is missing the import fails.
+"""
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libserveflow_hip.so")
+
+SF_OK, SF_EINVAL, SF_ENOMEM, SF_EHIP, SF_EUNSUPPORTED, SF_EDATA = 0, -1, -2, -3, -4, -5
+SF_F32, SF_BF16 = 0, 1
+SF_MAX_WINDOWS = 4
+
+EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf_featurize",
+           "sf_validate_packets", "sf_fast_infer", "sf_validate_forest", "sf_route",
+           "sf_vmin_from_theta", "sf_slow_infer")
+
+
+class SfPackets(ctypes.Structure):
+    _fields_ = [("n_flows", ctypes.c_uint32), ("n_pkts", ctypes.c_uint64),
+                ("flow_off", ctypes.c_void_p), ("pkt_size", ctypes.c_void_p),
+                ("pkt_iat", ctypes.c_void_p), ("pkt_dir", ctypes.c_void_p),
+                ("pkt_hdr", ctypes.c_void_p), ("hdr_words", ctypes.c_uint32)]
+
+
+class SfFeatCfg(ctypes.Structure):
+    _fields_ = [("n_windows", ctypes.c_uint32), ("depth", ctypes.c_uint32 * SF_MAX_WINDOWS),
+                ("raw_pkts", ctypes.c_uint32), ("raw_bits", ctypes.c_uint32)]
+
+
+class SfForest(ctypes.Structure):
+    _fields_ = [("n_trees", ctypes.c_uint32), ("depth", ctypes.c_uint32),
+                ("n_classes", ctypes.c_uint32), ("n_features", ctypes.c_uint32),
+                ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p),
+                ("leaf_label", ctypes.c_void_p)]
+
+
+class SfMlp(ctypes.Structure):
+    _fields_ = [("n_in", ctypes.c_uint32), ("n_h1", ctypes.c_uint32), ("n_h2", ctypes.c_uint32),
+                ("n_classes", ctypes.c_uint32), ("dtype", ctypes.c_int),
+                ("mu", ctypes.c_void_p), ("inv_sigma", ctypes.c_void_p), ("clamp", ctypes.c_float),
+                ("w1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("w3", ctypes.c_void_p),
+                ("b1", ctypes.c_void_p), ("b2", ctypes.c_void_p), ("b3", ctypes.c_void_p)]
+
+
+class ServeFlowError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("serveflow error %d: %s" % (code, text))
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library (python -m paper_2402_03694_amd.build makes it).  Raises if absent."""
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: build it with paper_2402_03694_amd.build.build()" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u32, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_size_t
+    lib.sf_workspace_bytes.restype = sz
+    lib.sf_workspace_bytes.argtypes = [u32] * 5
+    lib.sf_create.restype = ctypes.c_int
+    lib.sf_create.argtypes = [ctypes.POINTER(vp), vp, vp, sz]
+    lib.sf_destroy.restype = None
+    lib.sf_destroy.argtypes = [vp]
+    lib.sf_last_error.restype = ctypes.c_char_p
+    lib.sf_last_error.argtypes = [vp]
+    lib.sf_featurize.restype = ctypes.c_int
+    lib.sf_featurize.argtypes = [vp, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), vp, u32, vp]
+    lib.sf_validate_packets.restype = ctypes.c_int
+    lib.sf_validate_packets.argtypes = [vp, ctypes.POINTER(SfPackets)]
+    lib.sf_fast_infer.restype = ctypes.c_int
+    lib.sf_fast_infer.argtypes = [vp, vp, u32, u32, ctypes.POINTER(SfForest), vp, vp, vp, vp]
+    lib.sf_validate_forest.restype = ctypes.c_int
+    lib.sf_validate_forest.argtypes = [vp, ctypes.POINTER(SfForest)]
+    lib.sf_route.restype = ctypes.c_int
+    lib.sf_route.argtypes = [vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
+    lib.sf_vmin_from_theta.restype = u32
+    lib.sf_vmin_from_theta.argtypes = [ctypes.c_float, u32]
+    lib.sf_slow_infer.restype = ctypes.c_int
+    lib.sf_slow_infer.argtypes = [vp, vp, u32, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), vp, vp,
+                                  u32, u32, ctypes.POINTER(SfMlp), vp, vp]
+    return lib
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("expected a device tensor")
+    if not t.is_contiguous():
+        raise TypeError("expected a contiguous tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def sf_workspace_bytes(max_flows: int, n_trees: int = 0, tree_depth: int = 0, n_h1: int = 0, n_h2: int = 0) -> int:
+    return int(lib().sf_workspace_bytes(max_flows, n_trees, tree_depth, n_h1, n_h2))
+
+
+def sf_vmin_from_theta(theta: float, n_trees: int) -> int:
+    return int(lib().sf_vmin_from_theta(ctypes.c_float(theta), n_trees))
+
+
+class DevicePackets:
+    """Packet records on the device (SoA, CSR by flow)."""
+
+    def __init__(self, flow_off, pkt_size, pkt_iat, pkt_dir, pkt_hdr=None):
+        self.flow_off, self.pkt_size, self.pkt_iat, self.pkt_dir, self.pkt_hdr = flow_off, pkt_size, pkt_iat, pkt_dir, pkt_hdr
+        self.n_flows = int(flow_off.shape[0]) - 1
+        self.n_pkts = int(pkt_size.shape[0])
+
+    def c_struct(self) -> SfPackets:
+        # uint16/uint32 tensors are carried as int16/int32 storage of the same bits
+        s = SfPackets()
+        s.n_flows, s.n_pkts = self.n_flows, self.n_pkts
+        s.flow_off = _ptr(self.flow_off, torch.int32).value
+        s.pkt_size = _ptr(self.pkt_size, torch.int16).value if self.n_pkts else None
+        s.pkt_iat = _ptr(self.pkt_iat, torch.float32).value if self.n_pkts else None
+        s.pkt_dir = _ptr(self.pkt_dir, torch.uint8).value if self.n_pkts else None
+        if self.pkt_hdr is not None:
+            s.pkt_hdr = _ptr(self.pkt_hdr, torch.int32).value
+            s.hdr_words = int(self.pkt_hdr.shape[1])
+        return s
+
+
+class DeviceForest:
+    def __init__(self, n_trees, depth, n_classes, n_features, node_feat, node_thr, leaf_label):
+        self.n_trees, self.depth, self.n_classes, self.n_features = n_trees, depth, n_classes, n_features
+        self.node_feat, self.node_thr, self.leaf_label = node_feat, node_thr, leaf_label
+
+    def c_struct(self) -> SfForest:
+        s = SfForest()
+        s.n_trees, s.depth, s.n_classes, s.n_features = self.n_trees, self.depth, self.n_classes, self.n_features
+        s.node_feat = _ptr(self.node_feat, torch.int16).value
+        s.node_thr = _ptr(self.node_thr, torch.float32).value
+        s.leaf_label = _ptr(self.leaf_label, torch.uint8).value
+        return s
+
+
+class DeviceMlp:
+    """Weights row-major [out][in]: float32 for SF_F32, bfloat16 for SF_BF16; biases float32."""
+
+    def __init__(self, dims, dtype, w1, b1, w2, b2, w3, b3, mu=None, inv_sigma=None, clamp=8.0):
+        self.dims, self.dtype = tuple(dims), dtype
+        self.w1, self.b1, self.w2, self.b2, self.w3, self.b3 = w1, b1, w2, b2, w3, b3
+        self.mu, self.inv_sigma, self.clamp = mu, inv_sigma, clamp
+
+    def c_struct(self) -> SfMlp:
+        s = SfMlp()
+        s.n_in, s.n_h1, s.n_h2, s.n_classes = self.dims
+        s.dtype = self.dtype
+        wd = torch.float32 if self.dtype == SF_F32 else torch.bfloat16
+        s.mu = _ptr(self.mu, torch.float32).value if self.mu is not None else None
+        s.inv_sigma = _ptr(self.inv_sigma, torch.float32).value if self.inv_sigma is not None else None
+        s.clamp = self.clamp
+        s.w1, s.w2, s.w3 = (_ptr(w, wd).value for w in (self.w1, self.w2, self.w3))
+        s.b1, s.b2, s.b3 = (_ptr(b, torch.float32).value for b in (self.b1, self.b2, self.b3))
+        return s
+
+
+def _feat_cfg(depths: Sequence[int], raw_pkts: int = 0, raw_bits: int = 0) -> SfFeatCfg:
+    c = SfFeatCfg()
+    if len(depths) > SF_MAX_WINDOWS:
+        raise ServeFlowError(SF_EINVAL, "more than %d windows" % SF_MAX_WINDOWS)
+    c.n_windows = len(depths)
+    for i, d in enumerate(depths):
+        c.depth[i] = int(d)
+    c.raw_pkts, c.raw_bits = raw_pkts, raw_bits
+    return c
+
+
+class ServeFlow:
+    """One library context: a HIP stream plus a device workspace (a torch tensor it keeps alive)."""
+
+    def __init__(self, workspace_bytes: int, stream: Optional[torch.cuda.Stream] = None, device="cuda:0"):
+        self._h = None
+        self._lib = lib()
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.stream = stream
+        self.workspace = torch.empty(max(int(workspace_bytes), 256) + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        aligned = (base + 255) // 256 * 256
+        h = ctypes.c_void_p()
+        sptr = ctypes.c_void_p(stream.cuda_stream) if stream is not None else ctypes.c_void_p(
+            torch.cuda.current_stream(self.device).cuda_stream)
+        rc = self._lib.sf_create(ctypes.byref(h), sptr, ctypes.c_void_p(aligned),
+                                 int(self.workspace.numel() - (aligned - base)))
+        if rc != SF_OK:
+            raise ServeFlowError(rc, self._lib.sf_last_error(None).decode())
+        self._h = h
+
+    def close(self):
+        if self._h is not None:
+            self._lib.sf_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != SF_OK:
+            raise ServeFlowError(rc, self._lib.sf_last_error(self._h).decode())
+
+    # ---- the four steps, named as in the C ABI --------------------------------------------
+    def sf_featurize(self, pk: DevicePackets, depths: Sequence[int], feat: torch.Tensor,
+                     raw: Optional[torch.Tensor] = None, raw_pkts: int = 0, raw_bits: int = 0):
+        s, c = pk.c_struct(), _feat_cfg(depths, raw_pkts, raw_bits)
+        self._check(self._lib.sf_featurize(self._h, ctypes.byref(s), ctypes.byref(c), _ptr(feat, torch.float32),
+                                           int(feat.shape[1]) if feat.dim() == 2 else 0, _ptr(raw, torch.uint8)))
+
+    def sf_validate_packets(self, pk: DevicePackets):
+        s = pk.c_struct()
+        self._check(self._lib.sf_validate_packets(self._h, ctypes.byref(s)))
+
+    def sf_fast_infer(self, feat: torch.Tensor, forest: DeviceForest, pred: torch.Tensor, top_votes: torch.Tensor,
+                      votes: Optional[torch.Tensor] = None, leaf_idx: Optional[torch.Tensor] = None,
+                      n_flows: Optional[int] = None):
+        f = forest.c_struct()
+        n = int(feat.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_fast_infer(self._h, _ptr(feat, torch.float32), int(feat.shape[1]), n, ctypes.byref(f),
+                                            _ptr(votes, torch.int16), _ptr(pred, torch.int16),
+                                            _ptr(top_votes, torch.int16), _ptr(leaf_idx, torch.int16)))
+
+    def sf_validate_forest(self, forest: DeviceForest):
+        f = forest.c_struct()
+        self._check(self._lib.sf_validate_forest(self._h, ctypes.byref(f)))
+
+    def sf_route(self, top_votes: torch.Tensor, pred: Optional[torch.Tensor], vmin, esc_idx: torch.Tensor,
+                 esc_count: torch.Tensor, n_flows: Optional[int] = None):
+        vm = [int(vmin)] if isinstance(vmin, int) else [int(v) for v in vmin]
+        arr = (ctypes.c_uint16 * len(vm))(*vm)
+        n = int(top_votes.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_route(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr, len(vm),
+                                       _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_slow_infer(self, mlp: DeviceMlp, esc_idx: torch.Tensor, esc_count: torch.Tensor, labels: torch.Tensor,
+                      feat: Optional[torch.Tensor] = None, raw_src: Optional[DevicePackets] = None,
+                      raw_pkts: int = 0, raw_bits: int = 0, logits: Optional[torch.Tensor] = None,
+                      esc_cap: Optional[int] = None):
+        m = mlp.c_struct()
+        n = int(labels.shape[0])
+        cap = n if esc_cap is None else int(esc_cap)
+        if logits is not None:
+            cap = min(cap, int(logits.shape[0]))
+        s = raw_src.c_struct() if raw_src is not None else None
+        c = _feat_cfg([1], raw_pkts, raw_bits) if raw_src is not None else None
+        self._check(self._lib.sf_slow_infer(
+            self._h, _ptr(feat, torch.float32), int(feat.shape[1]) if feat is not None else 0,
+            ctypes.byref(s) if s is not None else None, ctypes.byref(c) if c is not None else None,
+            _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32), cap, n, ctypes.byref(m),
+            _ptr(logits, torch.float32), _ptr(labels, torch.int16)))

@@ -1,0 +1,181 @@
+// Step 4: the gate of Section 3.2 of the paper in integer form, and the compaction of the
+// uncertain flows into an ascending index list.
+//
+// Two launches, no spinning between blocks: the first counts the escalated flows of each
+// block's contiguous chunk; the second adds up the counts of the blocks before it, then
+// re-evaluates the gate and writes the indices in order (a wave-level prefix sum of per-lane
+// pop-counts gives each lane its write position).  The count stays on the device.
+#include "common.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kPerLane = 8;                // consecutive flows per lane per tile
+constexpr int kTile = kBlock * kPerLane;   // flows per block per tile
+constexpr uint32_t kMaxBlocks = 4096;
+
+struct RouteArgs {
+    const uint16_t* top;
+    const uint16_t* pred;
+    uint32_t n;
+    uint32_t chunk; // flows per block, a multiple of kTile
+    uint32_t n_vmin;
+    uint16_t vmin[SF_MAX_CLASSES];
+    uint32_t* counts;
+    uint32_t* esc_idx;
+    uint32_t* esc_count;
+};
+
+// 8-bit mask of the lane's flows [base, base+8) that escalate
+__device__ __forceinline__ uint32_t gate_mask(const RouteArgs& a, uint32_t base)
+{
+    uint32_t m = 0;
+    if (base >= a.n) return 0;
+    if (base + kPerLane <= a.n && a.n_vmin == 1) {
+        // base is a multiple of 8: the 16-byte load is aligned whenever top is
+        uint16_t v[kPerLane];
+        if ((reinterpret_cast<uintptr_t>(a.top) & 15u) == 0) {
+            const uint4 w = *reinterpret_cast<const uint4*>(a.top + base);
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                v[2 * k] = (uint16_t)(ww[k] & 0xFFFFu);
+                v[2 * k + 1] = (uint16_t)(ww[k] >> 16);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) v[k] = a.top[base + k];
+        }
+        const uint16_t th = a.vmin[0];
+#pragma unroll
+        for (int k = 0; k < kPerLane; ++k) m |= (v[k] < th ? 1u : 0u) << k;
+        return m;
+    }
+    for (int k = 0; k < kPerLane; ++k) {
+        const uint32_t i = base + k;
+        if (i < a.n) {
+            uint16_t th = a.vmin[0];
+            if (a.n_vmin > 1) {
+                uint32_t p = a.pred[i];
+                p = p < a.n_vmin ? p : a.n_vmin - 1;
+                th = a.vmin[p];
+            }
+            m |= (a.top[i] < th ? 1u : 0u) << k;
+        }
+    }
+    return m;
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// exclusive prefix of v over the block and the block total; sm holds kBlock/64 + 1 words
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* sm, uint32_t& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t inc = wave_inclusive_scan(v);
+    __syncthreads(); // sm may still be read from the previous tile
+    if (lane == 63) sm[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) {
+        const uint32_t s = sm[w];
+        before += w < wave ? s : 0;
+        tot += s;
+    }
+    total = tot;
+    return before + inc - v;
+}
+
+__global__ __launch_bounds__(kBlock) void route_count(RouteArgs a)
+{
+    __shared__ uint32_t sm[kBlock / 64];
+    const uint32_t begin = blockIdx.x * a.chunk;
+    uint32_t c = 0;
+    for (uint32_t t = 0; t < a.chunk; t += kTile) c += __popc(gate_mask(a, begin + t + threadIdx.x * kPerLane));
+    const uint32_t inc = wave_inclusive_scan(c);
+    if ((threadIdx.x & 63) == 63) sm[threadIdx.x >> 6] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t tot = 0;
+        for (int w = 0; w < kBlock / 64; ++w) tot += sm[w];
+        a.counts[blockIdx.x] = tot;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void route_scatter(RouteArgs a)
+{
+    __shared__ uint32_t sm[kBlock / 64];
+    // sum of the counts of all earlier blocks (every lane ends up with the block-wide total)
+    uint32_t part = 0;
+    for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kBlock) part += a.counts[b];
+    uint32_t run;
+    block_exclusive_scan(part, sm, run);
+    const uint32_t begin = blockIdx.x * a.chunk;
+    for (uint32_t t = 0; t < a.chunk; t += kTile) {
+        const uint32_t base = begin + t + threadIdx.x * kPerLane;
+        const uint32_t m = gate_mask(a, base);
+        uint32_t tile_total;
+        uint32_t pos = run + block_exclusive_scan(__popc(m), sm, tile_total);
+#pragma unroll
+        for (int k = 0; k < kPerLane; ++k)
+            if (m & (1u << k)) a.esc_idx[pos++] = base + k;
+        run += tile_total;
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *a.esc_count = run;
+}
+
+__global__ void route_zero(uint32_t* esc_count) { *esc_count = 0; }
+
+} // namespace
+
+extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
+                        const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route: ctx is NULL");
+    if (!host_vmin || n_vmin < 1 || n_vmin > SF_MAX_CLASSES)
+        return sf::fail(ctx, SF_EINVAL, "sf_route: host_vmin missing or n_vmin %u outside 1..%d", n_vmin,
+                        SF_MAX_CLASSES);
+    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route: esc_count is NULL");
+    if (n_flows == 0) {
+        route_zero<<<1, 1, 0, ctx->stream>>>(esc_count);
+        SF_LAUNCH_CHECK(ctx, "route_zero");
+        return SF_OK;
+    }
+    if (n_flows > (1u << 31)) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route: more than 2^31 flows per call");
+    if (!top_votes || !esc_idx) return sf::fail(ctx, SF_EINVAL, "sf_route: top_votes or esc_idx is NULL");
+    if (n_vmin > 1 && !pred) return sf::fail(ctx, SF_EINVAL, "sf_route: per-class thresholds need pred");
+
+    sf::Carve ws(ctx);
+    // workspace contents do not outlive a call: every entry point carves from the start
+    uint32_t* counts = (uint32_t*)ws.take(sf::route_scratch_bytes(n_flows));
+    if (!counts) return sf::fail(ctx, SF_ENOMEM, "sf_route: workspace too small for %zu bytes of block counts",
+                                 sf::route_scratch_bytes(n_flows));
+    RouteArgs a;
+    a.top = top_votes;
+    a.pred = pred;
+    a.n = n_flows;
+    uint64_t tiles = ((uint64_t)n_flows + kTile - 1) / kTile;
+    uint64_t tiles_per_block = (tiles + kMaxBlocks - 1) / kMaxBlocks;
+    a.chunk = (uint32_t)(tiles_per_block * kTile);
+    const uint32_t grid = (uint32_t)((tiles + tiles_per_block - 1) / tiles_per_block);
+    a.n_vmin = n_vmin;
+    for (uint32_t c = 0; c < SF_MAX_CLASSES; ++c) a.vmin[c] = host_vmin[c < n_vmin ? c : n_vmin - 1];
+    a.counts = counts;
+    a.esc_idx = esc_idx;
+    a.esc_count = esc_count;
+    route_count<<<grid, kBlock, 0, ctx->stream>>>(a);
+    SF_LAUNCH_CHECK(ctx, "route_count");
+    route_scatter<<<grid, kBlock, 0, ctx->stream>>>(a);
+    SF_LAUNCH_CHECK(ctx, "route_scatter");
+    return SF_OK;
+}

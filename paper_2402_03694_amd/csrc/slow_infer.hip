@@ -1,0 +1,557 @@
+// Step 5: the slow model on the escalated flows only; its label replaces the fast one
+// (Sections 3.1 and 4.4 of the paper).  The slow model is a 3-layer ReLU MLP.
+//
+// bfloat16 models run on the matrix cores: each layer is one tiled GEMM
+// C[rows][N] = act(A[rows][K] * W[N][K]^T + b) built from 32x32x16 MFMA blocks with binary32
+// accumulators.  Both operands are contiguous along K, which is exactly what an MFMA operand
+// wants (each lane supplies 8 consecutive K values of one row or column).  The first layer
+// builds its A tile on the fly from the escalated flows' feature rows (gather through the
+// index list, standardise, clamp, round to bfloat16) or from packed header bits; the last
+// layer adds the bias, finds the arg-max per row and scatters the label to the flow's slot.
+// The row count comes from the device-side escalation count; blocks past it exit.
+//
+// binary32 models (small, used for the small workload) run on plain vector arithmetic.
+#include "common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BM = 128; // rows per block
+constexpr int BK = 64;  // K per main-loop step
+constexpr int LDT = BK + 8; // shared-memory row stride (elements): 144 bytes keeps 16-byte
+                            // reads of 8 consecutive rows on distinct banks
+
+enum { A_BF16 = 0, A_FEAT = 1, A_RAW = 2 };
+
+struct LayerArgs {
+    // rows
+    const uint32_t* esc_idx;
+    const uint32_t* esc_count;
+    uint32_t esc_cap;
+    uint32_t row_begin; // first escalated row of this chunk
+    // A operand
+    const uint16_t* a_bf16; // [rows_in_chunk][lda]
+    uint32_t lda;
+    const float* feat;
+    uint32_t feat_ld;
+    const float* mu;
+    const float* inv_sigma;
+    float clamp;
+    const uint32_t* off;
+    const uint32_t* hdr;
+    uint32_t hdr_words, raw_bits, raw_pkts, n_pkts;
+    // weights
+    const uint16_t* w; // [N][K] bfloat16 bit patterns
+    const float* bias;
+    uint32_t N, K;
+    // output
+    uint16_t* h_out; // [rows_in_chunk][ldh] bfloat16
+    uint32_t ldh;
+    float* logits;   // [esc_cap][N] or NULL
+    uint16_t* labels;
+};
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16); // inf / nan: truncate
+    u += 0x7FFFu + ((u >> 16) & 1u);                                  // round to nearest even
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
+
+// 8 consecutive K values [k, k+8) of escalated row e as bfloat16, zero past K.
+template <int AMODE>
+__device__ __forceinline__ uint4 load_a_chunk(const LayerArgs& a, bool row_ok, uint32_t row_in_chunk,
+                                              uint32_t flow, uint32_t k)
+{
+    uint4 out = make_uint4(0, 0, 0, 0);
+    if (!row_ok || k >= a.K) return out;
+    if (AMODE == A_BF16) {
+        const uint16_t* p = a.a_bf16 + (size_t)row_in_chunk * a.lda + k;
+        if (k + 8 <= a.K && (a.lda & 7u) == 0) return *reinterpret_cast<const uint4*>(p);
+        uint16_t v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = k + q < a.K ? p[q] : (uint16_t)0;
+        return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+    }
+    if (AMODE == A_FEAT) {
+        const float* p = a.feat + (size_t)flow * a.feat_ld + k;
+        float x[8];
+        if (k + 8 <= a.K && (a.feat_ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0 && (k & 3u) == 0) {
+            const float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
+            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w;
+            x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) x[q] = k + q < a.K ? p[q] : 0.f;
+        }
+        uint16_t v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float z = x[q];
+            if (a.mu && k + q < a.K) {
+                const float d = z - a.mu[k + q];
+                z = d * a.inv_sigma[k + q];
+                z = z < -a.clamp ? -a.clamp : z;
+                z = z > a.clamp ? a.clamp : z;
+            }
+            v[q] = k + q < a.K ? f32_to_bf16_bits(z) : (uint16_t)0;
+        }
+        return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+    }
+    // A_RAW: feature k = raw_bits * packet + bit; bit b is bit 7-(b%8) of header byte b/8
+    uint32_t b0 = a.off[flow], e0 = a.off[flow + 1];
+    b0 = b0 < a.n_pkts ? b0 : a.n_pkts;
+    e0 = e0 < a.n_pkts ? e0 : a.n_pkts;
+    const uint32_t n = e0 > b0 ? e0 - b0 : 0;
+    uint16_t v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t kk = k + q;
+        uint16_t bit = 0;
+        if (kk < a.K) {
+            const uint32_t j = kk / a.raw_bits, b = kk - j * a.raw_bits;
+            if (j < n) {
+                const uint32_t byte_i = b >> 3;
+                const uint32_t word = a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)];
+                const uint32_t byte = (word >> (8u * (byte_i & 3u))) & 0xFFu;
+                bit = (uint16_t)((byte >> (7u - (b & 7u))) & 1u);
+            }
+        }
+        v[q] = bit ? (uint16_t)0x3F80 : (uint16_t)0; // bfloat16 1.0 or 0.0
+    }
+    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+}
+
+__device__ __forceinline__ uint4 load_w_chunk(const LayerArgs& a, uint32_t n, uint32_t k)
+{
+    if (n >= a.N || k >= a.K) return make_uint4(0, 0, 0, 0);
+    const uint16_t* p = a.w + (size_t)n * a.K + k;
+    if (k + 8 <= a.K && (a.K & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.w) & 15u) == 0)
+        return *reinterpret_cast<const uint4*>(p);
+    uint16_t v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = k + q < a.K ? p[q] : (uint16_t)0;
+    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u)
+{
+    union {
+        uint4 u;
+        bf16x8 b;
+    } c;
+    c.u = u;
+    return c.b;
+}
+
+// One layer.  BN = columns per block; FINAL = last layer (logits, arg-max, label scatter).
+template <int AMODE, int BN, bool FINAL>
+__global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
+{
+    constexpr int WAVES_N = BN >= 128 ? 2 : 1;
+    constexpr int WAVES_M = 4 / WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N; // wave tile
+    constexpr int MI = WM / 32, NI = WN / 32;
+    constexpr int A_CHUNKS = BM * BK / 8 / 256; // 16-byte chunks per thread per step
+    constexpr int B_CHUNKS = (BN * BK / 8 + 255) / 256;
+    constexpr int SM_AB = (BM + BN) * LDT * 2;
+    constexpr int SM_EPI = FINAL ? BM * (BN + 1) * 4 : 0;
+    constexpr int SM_BYTES = SM_AB > SM_EPI ? SM_AB : SM_EPI;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SM_BYTES];
+    __shared__ uint32_t s_flow[BM];
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Bs = As + BM * LDT;
+
+    uint32_t total = *a.esc_count;
+    total = total < a.esc_cap ? total : a.esc_cap;
+    const uint32_t row0 = a.row_begin + blockIdx.x * BM; // first escalated row of this block
+    if (row0 >= total) return;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const uint32_t col0 = blockIdx.y * BN;
+
+    if (AMODE != A_BF16 || FINAL) {
+        if (tid < BM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : 0u;
+        __syncthreads();
+    }
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    for (uint32_t k0 = 0; k0 < a.K; k0 += BK) {
+        uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+#pragma unroll
+        for (int u = 0; u < A_CHUNKS; ++u) {
+            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
+            const bool ok = row0 + r < total;
+            const uint32_t flow = (AMODE != A_BF16) ? s_flow[r] : 0u;
+            ra[u] = load_a_chunk<AMODE>(a, ok, blockIdx.x * BM + r, flow, k0 + kq * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < B_CHUNKS; ++u) {
+            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
+            rb[u] = (r < (uint32_t)BN) ? load_w_chunk(a, col0 + r, k0 + kq * 8) : make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads(); // previous step's fragment reads are done
+#pragma unroll
+        for (int u = 0; u < A_CHUNKS; ++u) {
+            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
+            *reinterpret_cast<uint4*>(As + r * LDT + kq * 8) = ra[u];
+        }
+#pragma unroll
+        for (int u = 0; u < B_CHUNKS; ++u) {
+            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
+            if (r < (uint32_t)BN) *reinterpret_cast<uint4*>(Bs + r * LDT + kq * 8) = rb[u];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[MI], fb[NI];
+            const uint32_t kofs = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                fa[i] = as_bf16x8(*reinterpret_cast<const uint4*>(As + (wm * WM + i * 32 + (lane & 31)) * LDT + kofs));
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                fb[j] = as_bf16x8(*reinterpret_cast<const uint4*>(Bs + (wn * WN + j * 32 + (lane & 31)) * LDT + kofs));
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // accumulator element v of lane l in a 32x32 block: row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    if (!FINAL) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const uint32_t col = col0 + wn * WN + j * 32 + (lane & 31);
+                const float b = col < a.N ? a.bias[col] : 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t r = wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    if (row0 + r < total && col < a.ldh) {
+                        float y = acc[i][j][v] + b;
+                        y = y > 0.f ? y : 0.f;
+                        // columns in [N, ldh) are padding: written as zeros
+                        a.h_out[(size_t)(blockIdx.x * BM + r) * a.ldh + col] = col < a.N ? f32_to_bf16_bits(y) : (uint16_t)0;
+                    }
+                }
+            }
+    } else {
+        __syncthreads(); // operand tiles are dead; reuse the space for the logits tile
+        float* Ls = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const uint32_t cl = wn * WN + j * 32 + (lane & 31);
+                const float b = col0 + cl < a.N ? a.bias[col0 + cl] : 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t r = wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    Ls[r * (BN + 1) + cl] = acc[i][j][v] + b;
+                }
+            }
+        __syncthreads();
+        if (tid < BM && row0 + tid < total) {
+            const float* lr = Ls + tid * (BN + 1);
+            uint32_t best = 0;
+            float bv = lr[0];
+            for (uint32_t c = 0; c < a.N; ++c) {
+                const float v = lr[c];
+                if (a.logits) a.logits[(size_t)(row0 + tid) * a.N + c] = v;
+                if (v > bv) {
+                    bv = v;
+                    best = c;
+                }
+            }
+            a.labels[s_flow[tid]] = (uint16_t)best;
+        }
+    }
+}
+
+// ---- binary32 model (plain vector arithmetic) ---------------------------------------------
+
+struct F32Args {
+    const uint32_t* esc_idx;
+    const uint32_t* esc_count;
+    uint32_t esc_cap, row_begin, rows_cap;
+    const float* feat;
+    uint32_t feat_ld;
+    const float* mu;
+    const float* inv_sigma;
+    float clamp;
+    const uint32_t* off;
+    const uint32_t* hdr;
+    uint32_t hdr_words, raw_bits, raw_pkts, n_pkts;
+    uint32_t n_in;
+};
+
+__global__ __launch_bounds__(256) void f32_input(F32Args a, float* __restrict__ z)
+{
+    uint32_t total = *a.esc_count;
+    total = total < a.esc_cap ? total : a.esc_cap;
+    if (a.row_begin >= total) return;
+    uint32_t rows = total - a.row_begin;
+    rows = rows < a.rows_cap ? rows : a.rows_cap;
+    const uint64_t n = (uint64_t)rows * a.n_in;
+    for (uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n; g += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t r = (uint32_t)(g / a.n_in), k = (uint32_t)(g % a.n_in);
+        const uint32_t flow = a.esc_idx[a.row_begin + r];
+        float v;
+        if (a.feat) {
+            v = a.feat[(size_t)flow * a.feat_ld + k];
+            if (a.mu) {
+                const float d = v - a.mu[k];
+                v = d * a.inv_sigma[k];
+                v = v < -a.clamp ? -a.clamp : v;
+                v = v > a.clamp ? a.clamp : v;
+            }
+        } else {
+            uint32_t b0 = a.off[flow], e0 = a.off[flow + 1];
+            b0 = b0 < a.n_pkts ? b0 : a.n_pkts;
+            e0 = e0 < a.n_pkts ? e0 : a.n_pkts;
+            const uint32_t np = e0 > b0 ? e0 - b0 : 0;
+            const uint32_t j = k / a.raw_bits, b = k - j * a.raw_bits;
+            v = 0.f;
+            if (j < np) {
+                const uint32_t byte_i = b >> 3;
+                const uint32_t word = a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)];
+                v = (float)(((word >> (8u * (byte_i & 3u))) >> (7u - (b & 7u))) & 1u);
+            }
+        }
+        z[g] = v;
+    }
+}
+
+// out[r][o] = act(sum_k in[r][k] * w[o][k] + b[o]); 64 rows x 4 outputs per block pass
+__global__ __launch_bounds__(256) void f32_layer(const uint32_t* esc_count, uint32_t esc_cap, uint32_t row_begin,
+                                                 uint32_t rows_cap, const float* __restrict__ in, uint32_t K,
+                                                 const float* __restrict__ w, const float* __restrict__ bias,
+                                                 uint32_t N, float* __restrict__ out, int relu)
+{
+    uint32_t total = *esc_count;
+    total = total < esc_cap ? total : esc_cap;
+    if (row_begin >= total) return;
+    uint32_t rows = total - row_begin;
+    rows = rows < rows_cap ? rows : rows_cap;
+    const uint64_t n = (uint64_t)rows * N;
+    for (uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n; g += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t r = (uint32_t)(g / N), o = (uint32_t)(g % N);
+        const float* x = in + (size_t)r * K;
+        const float* wr = w + (size_t)o * K;
+        float acc = 0.f;
+        for (uint32_t k = 0; k < K; ++k) acc += x[k] * wr[k];
+        acc += bias[o];
+        out[g] = (relu && acc < 0.f) ? 0.f : acc;
+    }
+}
+
+__global__ __launch_bounds__(256) void f32_argmax(const uint32_t* esc_idx, const uint32_t* esc_count, uint32_t esc_cap,
+                                                  uint32_t row_begin, uint32_t rows_cap, const float* __restrict__ lg,
+                                                  uint32_t C, float* __restrict__ logits, uint16_t* __restrict__ labels)
+{
+    uint32_t total = *esc_count;
+    total = total < esc_cap ? total : esc_cap;
+    if (row_begin >= total) return;
+    uint32_t rows = total - row_begin;
+    rows = rows < rows_cap ? rows : rows_cap;
+    for (uint32_t r = blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += gridDim.x * blockDim.x) {
+        const float* p = lg + (size_t)r * C;
+        uint32_t best = 0;
+        float bv = p[0];
+        for (uint32_t c = 0; c < C; ++c) {
+            const float v = p[c];
+            if (logits) logits[(size_t)(row_begin + r) * C + c] = v;
+            if (v > bv) {
+                bv = v;
+                best = c;
+            }
+        }
+        labels[esc_idx[row_begin + r]] = (uint16_t)best;
+    }
+}
+
+template <int AMODE>
+void launch_hidden(sf_ctx* ctx, const LayerArgs& a, uint32_t rows_cap)
+{
+    dim3 grid((rows_cap + BM - 1) / BM, (a.ldh + 127) / 128);
+    mlp_layer<AMODE, 128, false><<<grid, 256, 0, ctx->stream>>>(a);
+}
+
+void launch_final(sf_ctx* ctx, const LayerArgs& a, uint32_t rows_cap)
+{
+    dim3 grid((rows_cap + BM - 1) / BM, 1);
+    if (a.N <= 32)
+        mlp_layer<A_BF16, 32, true><<<grid, 256, 0, ctx->stream>>>(a);
+    else
+        mlp_layer<A_BF16, 64, true><<<grid, 256, 0, ctx->stream>>>(a);
+}
+
+uint32_t pad64(uint32_t x) { return (x + 63u) / 64u * 64u; }
+
+} // namespace
+
+extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_packets* raw_src,
+                             const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx, const uint32_t* esc_count,
+                             uint32_t esc_cap, uint32_t n_flows, const sf_mlp* mlp, float* logits, uint16_t* labels)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_slow_infer: ctx is NULL");
+    if (!mlp) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: mlp is NULL");
+    if (mlp->dtype != SF_F32 && mlp->dtype != SF_BF16) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: unknown dtype %d", mlp->dtype);
+    if (!mlp->n_in || !mlp->n_h1 || !mlp->n_h2 || !mlp->n_classes)
+        return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: a layer width is zero");
+    if (mlp->n_classes > SF_MAX_CLASSES)
+        return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: n_classes %u > %d", mlp->n_classes, SF_MAX_CLASSES);
+    if (!mlp->w1 || !mlp->w2 || !mlp->w3 || !mlp->b1 || !mlp->b2 || !mlp->b3)
+        return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: weights or biases missing");
+    if ((mlp->mu == nullptr) != (mlp->inv_sigma == nullptr))
+        return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: mu and inv_sigma come together");
+    if (n_flows == 0 || esc_cap == 0) return SF_OK;
+    if ((feat == nullptr) == (raw_src == nullptr))
+        return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: give exactly one of feat and raw_src");
+    if (feat && mlp->n_in > feat_ld) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: n_in %u > feat_ld %u", mlp->n_in, feat_ld);
+    if (raw_src) {
+        if (!raw_cfg || !raw_src->pkt_hdr || !raw_src->flow_off || raw_src->hdr_words == 0)
+            return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: raw input needs raw_cfg, flow_off and pkt_hdr");
+        if (raw_cfg->raw_bits == 0 || raw_cfg->raw_bits > 32 * raw_src->hdr_words ||
+            (uint64_t)raw_cfg->raw_pkts * raw_cfg->raw_bits != mlp->n_in)
+            return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: raw_pkts*raw_bits must equal n_in and fit the header words");
+        if (raw_src->n_flows != n_flows) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: raw_src->n_flows != n_flows");
+        if (raw_src->n_pkts >> 32) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: n_pkts exceeds 32-bit offsets");
+    }
+    if (!esc_idx || !esc_count || !labels) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: esc_idx, esc_count or labels is NULL");
+    if (esc_cap > n_flows) esc_cap = n_flows;
+
+    sf::Carve ws(ctx);
+    const bool bf = mlp->dtype == SF_BF16;
+    const uint32_t ld1 = bf ? pad64(mlp->n_h1) : mlp->n_h1, ld2 = bf ? pad64(mlp->n_h2) : mlp->n_h2;
+    const size_t row_bytes = bf ? ((size_t)ld1 + ld2) * 2 : ((size_t)mlp->n_in + ld1 + ld2 + mlp->n_classes) * 4;
+    const size_t avail = ws.left() > 4 * sf::kAlign ? ws.left() - 4 * sf::kAlign : 0;
+    uint64_t rows_cap = avail / row_bytes / BM * BM;
+    if (rows_cap < sf::kSlowMinRows)
+        return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace holds %llu rows of hidden activations, need at least %u",
+                        (unsigned long long)rows_cap, sf::kSlowMinRows);
+    if (rows_cap > ((uint64_t)esc_cap + BM - 1) / BM * BM) rows_cap = ((uint64_t)esc_cap + BM - 1) / BM * BM;
+    const uint32_t R = (uint32_t)rows_cap;
+
+    if (bf) {
+        uint16_t* h1 = (uint16_t*)ws.take((size_t)R * ld1 * 2);
+        uint16_t* h2 = (uint16_t*)ws.take((size_t)R * ld2 * 2);
+        if (!h1 || !h2) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace carve failed");
+        for (uint32_t begin = 0; begin < esc_cap; begin += R) {
+            LayerArgs a = {};
+            a.esc_idx = esc_idx;
+            a.esc_count = esc_count;
+            a.esc_cap = esc_cap;
+            a.row_begin = begin;
+            a.labels = labels;
+            // layer 1
+            a.feat = feat;
+            a.feat_ld = feat_ld;
+            a.mu = mlp->mu;
+            a.inv_sigma = mlp->inv_sigma;
+            a.clamp = mlp->clamp;
+            if (raw_src) {
+                a.off = raw_src->flow_off;
+                a.hdr = raw_src->pkt_hdr;
+                a.hdr_words = raw_src->hdr_words;
+                a.raw_bits = raw_cfg->raw_bits;
+                a.raw_pkts = raw_cfg->raw_pkts;
+                a.n_pkts = (uint32_t)raw_src->n_pkts;
+            }
+            a.w = (const uint16_t*)mlp->w1;
+            a.bias = mlp->b1;
+            a.N = mlp->n_h1;
+            a.K = mlp->n_in;
+            a.h_out = h1;
+            a.ldh = ld1;
+            if (raw_src)
+                launch_hidden<A_RAW>(ctx, a, R);
+            else
+                launch_hidden<A_FEAT>(ctx, a, R);
+            SF_LAUNCH_CHECK(ctx, "mlp_layer 1");
+            // layer 2
+            a.a_bf16 = h1;
+            a.lda = ld1;
+            a.w = (const uint16_t*)mlp->w2;
+            a.bias = mlp->b2;
+            a.N = mlp->n_h2;
+            a.K = mlp->n_h1;
+            a.h_out = h2;
+            a.ldh = ld2;
+            launch_hidden<A_BF16>(ctx, a, R);
+            SF_LAUNCH_CHECK(ctx, "mlp_layer 2");
+            // layer 3
+            a.a_bf16 = h2;
+            a.lda = ld2;
+            a.w = (const uint16_t*)mlp->w3;
+            a.bias = mlp->b3;
+            a.N = mlp->n_classes;
+            a.K = mlp->n_h2;
+            a.h_out = nullptr;
+            a.ldh = 0;
+            a.logits = logits;
+            launch_final(ctx, a, R);
+            SF_LAUNCH_CHECK(ctx, "mlp_layer 3");
+        }
+        return SF_OK;
+    }
+
+    float* z = (float*)ws.take((size_t)R * mlp->n_in * 4);
+    float* h1 = (float*)ws.take((size_t)R * ld1 * 4);
+    float* h2 = (float*)ws.take((size_t)R * ld2 * 4);
+    float* lg = (float*)ws.take((size_t)R * mlp->n_classes * 4);
+    if (!z || !h1 || !h2 || !lg) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace carve failed");
+    for (uint32_t begin = 0; begin < esc_cap; begin += R) {
+        F32Args f = {};
+        f.esc_idx = esc_idx;
+        f.esc_count = esc_count;
+        f.esc_cap = esc_cap;
+        f.row_begin = begin;
+        f.rows_cap = R;
+        f.feat = feat;
+        f.feat_ld = feat_ld;
+        f.mu = mlp->mu;
+        f.inv_sigma = mlp->inv_sigma;
+        f.clamp = mlp->clamp;
+        if (raw_src) {
+            f.off = raw_src->flow_off;
+            f.hdr = raw_src->pkt_hdr;
+            f.hdr_words = raw_src->hdr_words;
+            f.raw_bits = raw_cfg->raw_bits;
+            f.raw_pkts = raw_cfg->raw_pkts;
+            f.n_pkts = (uint32_t)raw_src->n_pkts;
+        }
+        f.n_in = mlp->n_in;
+        auto blocks = [&](uint64_t n) { uint64_t b = (n + 255) / 256; return (uint32_t)(b > 16384 ? 16384 : (b ? b : 1)); };
+        f32_input<<<blocks((uint64_t)R * mlp->n_in), 256, 0, ctx->stream>>>(f, z);
+        SF_LAUNCH_CHECK(ctx, "f32_input");
+        f32_layer<<<blocks((uint64_t)R * mlp->n_h1), 256, 0, ctx->stream>>>(esc_count, esc_cap, begin, R, z, mlp->n_in,
+                                                                            (const float*)mlp->w1, mlp->b1, mlp->n_h1, h1, 1);
+        SF_LAUNCH_CHECK(ctx, "f32_layer 1");
+        f32_layer<<<blocks((uint64_t)R * mlp->n_h2), 256, 0, ctx->stream>>>(esc_count, esc_cap, begin, R, h1, mlp->n_h1,
+                                                                            (const float*)mlp->w2, mlp->b2, mlp->n_h2, h2, 1);
+        SF_LAUNCH_CHECK(ctx, "f32_layer 2");
+        f32_layer<<<blocks((uint64_t)R * mlp->n_classes), 256, 0, ctx->stream>>>(
+            esc_count, esc_cap, begin, R, h2, mlp->n_h2, (const float*)mlp->w3, mlp->b3, mlp->n_classes, lg, 0);
+        SF_LAUNCH_CHECK(ctx, "f32_layer 3");
+        f32_argmax<<<blocks(R), 256, 0, ctx->stream>>>(esc_idx, esc_count, esc_cap, begin, R, lg, mlp->n_classes, logits, labels);
+        SF_LAUNCH_CHECK(ctx, "f32_argmax");
+    }
+    return SF_OK;
+}

@@ -1,0 +1,76 @@
+"""Runs the HIP path through the C ABI binding on seeded inputs and returns numpy results.
+Imports the product package only; the oracle is called by the tests, never from here."""
+import numpy as np
+import torch
+
+import paper_2402_03694_amd as sf
+
+
+def u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+class GpuRun:
+    """Device buffers for one workload; each step is one call through the binding."""
+
+    def __init__(self, cfg, pk, forest=None, mlp=None, ws_bytes=None, feat_ld=None, esc_cap=None):
+        self.cfg, self.n = cfg, pk.n_flows
+        dev = "cuda:0"
+        n = self.n
+        h1, h2 = (mlp.dims[1], mlp.dims[2]) if mlp is not None else (0, 0)
+        if ws_bytes is None:
+            ws_bytes = sf.sf_workspace_bytes(max(n, 1), cfg.n_trees, cfg.tree_depth, h1, h2)
+        self.ctx = sf.ServeFlow(ws_bytes)
+        self.pk = sf.packets_to_device(pk, dev)
+        self.forest = sf.forest_to_device(forest, dev) if forest is not None else None
+        self.mlp = sf.mlp_to_device(mlp, dev) if mlp is not None else None
+        F = cfg.n_features
+        self.ld = F if feat_ld is None else feat_ld
+        self.feat = torch.full((n, self.ld), -777.0, dtype=torch.float32, device=dev)
+        self.pred = torch.zeros(n, dtype=torch.int16, device=dev)
+        self.top = torch.zeros(n, dtype=torch.int16, device=dev)
+        self.votes = torch.zeros((n, cfg.n_classes), dtype=torch.int16, device=dev)
+        self.leaf = torch.zeros((n, cfg.n_trees), dtype=torch.int16, device=dev)
+        self.esc_idx = torch.full((max(n, 1),), -1, dtype=torch.int32, device=dev)
+        self.esc_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+        self.labels = torch.zeros(n, dtype=torch.int16, device=dev)
+        self.esc_cap = n if esc_cap is None else esc_cap
+        C = mlp.dims[3] if mlp is not None else 1
+        self.logits = torch.full((max(self.esc_cap, 1), C), float("nan"), dtype=torch.float32, device=dev)
+
+    def featurize(self, raw=False):
+        rawbuf = None
+        if raw:
+            rawbuf = torch.full((self.n, self.cfg.raw_pkts * self.cfg.raw_bits), 9, dtype=torch.uint8, device="cuda:0")
+        self.ctx.sf_featurize(self.pk, self.cfg.depths, self.feat, raw=rawbuf, raw_pkts=self.cfg.raw_pkts,
+                              raw_bits=self.cfg.raw_bits)
+        torch.cuda.synchronize()
+        return self.feat.cpu().numpy(), (rawbuf.cpu().numpy() if raw else None)
+
+    def fast_infer(self, want_leaf=True, want_votes=True):
+        self.ctx.sf_fast_infer(self.feat, self.forest, self.pred, self.top,
+                               votes=self.votes if want_votes else None, leaf_idx=self.leaf if want_leaf else None)
+        torch.cuda.synchronize()
+        return u16(self.votes), u16(self.pred), u16(self.top), u16(self.leaf)
+
+    def route(self, vmin):
+        self.ctx.sf_route(self.top, self.pred, vmin, self.esc_idx, self.esc_count)
+        torch.cuda.synchronize()
+        cnt = int(u32(self.esc_count)[0])
+        return u32(self.esc_idx)[:cnt].copy(), cnt
+
+    def slow_infer(self, use_raw=False):
+        self.labels.copy_(self.pred)
+        if use_raw:
+            self.ctx.sf_slow_infer(self.mlp, self.esc_idx, self.esc_count, self.labels, raw_src=self.pk,
+                                   raw_pkts=self.cfg.raw_pkts, raw_bits=self.cfg.raw_bits, logits=self.logits,
+                                   esc_cap=self.esc_cap)
+        else:
+            self.ctx.sf_slow_infer(self.mlp, self.esc_idx, self.esc_count, self.labels, feat=self.feat,
+                                   logits=self.logits, esc_cap=self.esc_cap)
+        torch.cuda.synchronize()
+        return self.logits.cpu().numpy(), u16(self.labels)
