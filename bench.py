@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Throughput of the whole hot path (featurize -> fast trees -> gate -> slow MLP) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+
+A step is one pass of all four calls over one batch of synthetic flows that is already resident
+in HBM.  Prints one JSON line: flows/s, ms per step, the roofline of the dominant kernel (and of
+every call, under "kernels"), and the CPU oracle timed on this host's cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+F32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def pick_vmin(top_votes: np.ndarray, n_trees: int, target: float):
+    """Target-portion rule of Section 3.2 on an integer score: the threshold whose escalated fraction
+    is nearest the target (ties -> the smaller fraction).  Host-side calibration, outside the timing."""
+    hist = np.bincount(top_votes, minlength=n_trees + 2).astype(np.float64)
+    below = np.concatenate([[0.0], np.cumsum(hist)])[: n_trees + 2] / top_votes.size   # frac with top < v
+    best = min(range(n_trees + 2), key=lambda v: (abs(below[v] - target), below[v]))
+    return best, float(below[best])
+
+
+def algorithmic_bytes(cfg, n_flows, n_pkts, esc_frac):
+    """Bytes the method itself must move per call (inputs read once + outputs written once)."""
+    F = cfg.n_features
+    k1 = 7 * n_pkts + 4 * (n_flows + 1) + 4 * F * n_flows           # packet records + offsets + features out
+    k2 = 4 * F * n_flows + 4 * n_flows                              # features in + pred/top out
+    k3 = 2 * n_flows + 4 * esc_frac * n_flows                       # scores in + index list out
+    return k1, k2, k3
+
+
+def mlp_flops(cfg, n_rows):
+    a, b, c, d = cfg.mlp_dims
+    return 2.0 * (a * b + b * c + c * d) * n_rows
+
+
+def cpu_baseline(cfg, sample_flows, vmin):
+    """The oracle as it stands, all four steps, on a bounded sample of the same workload."""
+    import oracle
+    import synth
+    threads = oracle.default_threads()
+    pk = synth.make_packets(cfg, n_flows=sample_flows)
+    calib, _ = oracle.featurize(pk.flow_off[: cfg.calib_flows + 1], pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths,
+                                n_threads=threads)
+    forest = synth.make_forest(cfg, calib)
+    mlp = synth.make_mlp(cfg, None if cfg.raw_pkts else calib)
+    t0 = time.perf_counter()
+    out = oracle.classify(pk, cfg.depths, forest, vmin, mlp, raw_pkts=cfg.raw_pkts, raw_bits=cfg.raw_bits,
+                          n_threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": sample_flows / dt, "unit": "flows/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d flows of the workload, all four steps, %.1f s wall, %.1f%% escalated"
+                      % (sample_flows, dt, 100.0 * out["esc_idx"].size / sample_flows)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the 1M-flow headline workload)")
+    ap.add_argument("--flows", type=int, default=0, help="override the flow count (for quick runs)")
+    ap.add_argument("--target", type=float, default=-1.0, help="override the escalated-fraction target")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (flows would be sharded "
+              "across devices with the models replicated, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2402_03694_amd as sf
+    from paper_2402_03694_amd import build as hip_build
+    if hip_build.is_stale():
+        hip_build.build(force=True)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+
+    cfg = synth.get_config(args.config)
+    n = args.flows or cfg.n_flows
+    pk = synth.make_packets(cfg, n_flows=n)
+    n_pkts = pk.n_pkts
+    F, C = cfg.n_features, cfg.n_classes
+    h1, h2 = cfg.mlp_dims[1], cfg.mlp_dims[2]
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, h1, h2))
+    d_pk = sf.packets_to_device(pk, dev)
+    feat = torch.empty((n, F), dtype=torch.float32, device=dev)
+    pred = torch.empty(n, dtype=torch.int16, device=dev)
+    top = torch.empty(n, dtype=torch.int16, device=dev)
+    esc_idx = torch.empty(n, dtype=torch.int32, device=dev)
+    esc_count = torch.zeros(1, dtype=torch.int32, device=dev)
+    labels = torch.empty(n, dtype=torch.int16, device=dev)
+
+    # models: thresholds and standardisation constants come from the first calib_flows flows' features
+    ctx.sf_featurize(d_pk, cfg.depths, feat)
+    torch.cuda.synchronize()
+    calib = feat[: cfg.calib_flows].cpu().numpy()
+    forest = synth.make_forest(cfg, calib)
+    mlp = synth.make_mlp(cfg, None if cfg.raw_pkts else calib)
+    d_forest, d_mlp = sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
+    ctx.sf_validate_packets(d_pk)
+    ctx.sf_validate_forest(d_forest)
+
+    # gate threshold: explicit, from theta, or the target-portion rule on this run's own scores
+    ctx.sf_fast_infer(feat, d_forest, pred, top)
+    torch.cuda.synchronize()
+    top_h = top.cpu().numpy().view(np.uint16)
+    if args.target >= 0:
+        vmin, frac = pick_vmin(top_h, cfg.n_trees, args.target)
+    elif cfg.vmin is not None:
+        vmin = cfg.vmin
+    elif cfg.theta is not None:
+        vmin = sf.sf_vmin_from_theta(cfg.theta, cfg.n_trees)
+    else:
+        vmin, frac = pick_vmin(top_h, cfg.n_trees, cfg.target_fracs[len(cfg.target_fracs) // 2])
+    frac = float((top_h < vmin).mean())
+    esc_cap = n
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        ctx.sf_featurize(d_pk, cfg.depths, feat)
+        if ev:
+            ev[1].record()
+        ctx.sf_fast_infer(feat, d_forest, pred, top)
+        if ev:
+            ev[2].record()
+        ctx.sf_route(top, pred, vmin, esc_idx, esc_count)
+        if ev:
+            ev[3].record()
+        if cfg.raw_pkts:
+            ctx.sf_slow_infer(d_mlp, esc_idx, esc_count, labels, raw_src=d_pk, raw_pkts=cfg.raw_pkts,
+                              raw_bits=cfg.raw_bits, esc_cap=esc_cap, pred=pred)
+        else:
+            ctx.sf_slow_infer(d_mlp, esc_idx, esc_count, labels, feat=feat, esc_cap=esc_cap, pred=pred)
+        if ev:
+            ev[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # HIP events on the stream the kernels run on (the context was created on torch's current stream)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    n_esc = int(esc_count.cpu().numpy().view(np.uint32)[0])
+    call_ms = np.array([[ev[i].elapsed_time(ev[i + 1]) for i in range(4)] for ev in events])   # [steps][4]
+    avg = call_ms.mean(axis=0)
+
+    k1b, k2b, k3b = algorithmic_bytes(cfg, n, n_pkts, n_esc / n)
+    flops = mlp_flops(cfg, n_esc)
+    visits = float(n) * cfg.n_trees * cfg.tree_depth
+
+    def hbm(bytes_, ms):
+        a = bytes_ / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
+                "traffic": None}
+
+    kernels = {
+        "sf_featurize": dict(hbm(k1b, avg[0]), ms=float(avg[0]), bytes=k1b),
+        "sf_fast_infer": dict(hbm(k2b, avg[1]), ms=float(avg[1]), bytes=k2b, node_visits=visits,
+                              visits_per_s=visits / (avg[1] * 1e-3)),
+        "sf_route": dict(hbm(k3b, avg[2]), ms=float(avg[2]), bytes=k3b),
+    }
+    tf = flops / (avg[3] * 1e-3) / 1e12
+    if cfg.mlp_dtype == "bf16":
+        kernels["sf_slow_infer"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                    "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "ms": float(avg[3]),
+                                    "flops": flops}
+    else:
+        kernels["sf_slow_infer"] = {"bound": "alu", "achieved": tf, "peak": F32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                    "frac": tf / F32_VECTOR_PEAK_TFLOPS, "traffic": None, "ms": float(avg[3]),
+                                    "flops": flops}
+    names = list(kernels)
+    dominant = names[int(np.argmax(avg))]
+    roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roof["kernel"] = dominant
+
+    out = {
+        "metric": "flows/sec end-to-end (fast+gated slow)",
+        "value": n * args.steps / (t1 - t0),
+        "unit": "flows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 features, integer votes, %s MLP" % cfg.mlp_dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: %d flows, %d packets, F=%d, T=%d depth %d C=%d, vmin=%d, MLP %s %s"
+                               % (cfg.name, n, n_pkts, F, cfg.n_trees, cfg.tree_depth, C, vmin, cfg.mlp_dtype,
+                                  "x".join(map(str, cfg.mlp_dims))),
+                   "escalated_fraction": n_esc / n, "calibrated_fraction": frac},
+        "roofline": roof,
+        "kernels": kernels,
+        "p50_ms": float(np.median(call_ms.sum(axis=1))), "p99_ms": float(np.percentile(call_ms.sum(axis=1), 99)),
+    }
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample or min(n, 1 << 18)
+        out["cpu_baseline"] = cpu_baseline(cfg, sample, vmin)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

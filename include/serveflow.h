@@ -178,14 +178,17 @@ typedef struct {
 } sf_mlp;
 
 /* esc_idx / esc_count: as written by sf_route (device).  At most esc_cap flows are
- * processed (the capacity of logits; pass n_flows to process all).  logits: optional
- * [esc_cap][n_classes].  labels: [n_flows], in/out: the caller pre-fills it with the fast
- * prediction; entries of escalated flows are overwritten with the slow label.
- * Exactly one of feat / raw_src is given.  Uses workspace for hidden activations. */
+ * processed (the capacity of logits; pass n_flows to process all); flows beyond it keep the
+ * fast label, and the caller can see that from *esc_count > esc_cap.  logits: optional
+ * [esc_cap][n_classes], row e belongs to flow esc_idx[e].  labels: [n_flows], the final
+ * label of every flow: pred[i] (the fast prediction, [n_flows]) unless flow i escalated,
+ * then the slow label.  pred may be NULL (or equal to labels) when the caller has already
+ * filled labels with the fast prediction.  Exactly one of feat / raw_src is given.
+ * Uses workspace for hidden activations. */
 int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_packets* raw_src,
                   const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx,
                   const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_flows,
-                  const sf_mlp* mlp, float* logits, uint16_t* labels);
+                  const sf_mlp* mlp, const uint16_t* pred, float* logits, uint16_t* labels);
 
 #ifdef __cplusplus
 }

@@ -84,7 +84,7 @@ def load_library() -> ctypes.CDLL:
     lib.sf_vmin_from_theta.argtypes = [ctypes.c_float, u32]
     lib.sf_slow_infer.restype = ctypes.c_int
     lib.sf_slow_infer.argtypes = [vp, vp, u32, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), vp, vp,
-                                  u32, u32, ctypes.POINTER(SfMlp), vp, vp]
+                                  u32, u32, ctypes.POINTER(SfMlp), vp, vp, vp]
     return lib
 
 
@@ -257,7 +257,7 @@ class ServeFlow:
     def sf_slow_infer(self, mlp: DeviceMlp, esc_idx: torch.Tensor, esc_count: torch.Tensor, labels: torch.Tensor,
                       feat: Optional[torch.Tensor] = None, raw_src: Optional[DevicePackets] = None,
                       raw_pkts: int = 0, raw_bits: int = 0, logits: Optional[torch.Tensor] = None,
-                      esc_cap: Optional[int] = None):
+                      esc_cap: Optional[int] = None, pred: Optional[torch.Tensor] = None):
         m = mlp.c_struct()
         n = int(labels.shape[0])
         cap = n if esc_cap is None else int(esc_cap)
@@ -269,4 +269,4 @@ class ServeFlow:
             self._h, _ptr(feat, torch.float32), int(feat.shape[1]) if feat is not None else 0,
             ctypes.byref(s) if s is not None else None, ctypes.byref(c) if c is not None else None,
             _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32), cap, n, ctypes.byref(m),
-            _ptr(logits, torch.float32), _ptr(labels, torch.int16)))
+            _ptr(pred, torch.int16), _ptr(logits, torch.float32), _ptr(labels, torch.int16)))

@@ -402,13 +402,25 @@ void launch_final(sf_ctx* ctx, const LayerArgs& a, uint32_t rows_cap)
         mlp_layer<A_BF16, 64, true><<<grid, 256, 0, ctx->stream>>>(a);
 }
 
+// labels = pred for every flow; the slow labels are scattered over it afterwards
+__global__ __launch_bounds__(256) void copy_labels(const uint16_t* __restrict__ pred, uint16_t* __restrict__ labels, uint32_t n)
+{
+    const uint32_t base = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (base + 8 <= n && ((reinterpret_cast<uintptr_t>(pred) | reinterpret_cast<uintptr_t>(labels)) & 15u) == 0) {
+        *reinterpret_cast<uint4*>(labels + base) = *reinterpret_cast<const uint4*>(pred + base);
+    } else {
+        for (uint32_t k = base; k < n && k < base + 8; ++k) labels[k] = pred[k];
+    }
+}
+
 uint32_t pad64(uint32_t x) { return (x + 63u) / 64u * 64u; }
 
 } // namespace
 
 extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_packets* raw_src,
                              const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx, const uint32_t* esc_count,
-                             uint32_t esc_cap, uint32_t n_flows, const sf_mlp* mlp, float* logits, uint16_t* labels)
+                             uint32_t esc_cap, uint32_t n_flows, const sf_mlp* mlp, const uint16_t* pred, float* logits,
+                             uint16_t* labels)
 {
     if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_slow_infer: ctx is NULL");
     if (!mlp) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: mlp is NULL");
@@ -436,6 +448,11 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
     }
     if (!esc_idx || !esc_count || !labels) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: esc_idx, esc_count or labels is NULL");
     if (esc_cap > n_flows) esc_cap = n_flows;
+    if (pred && pred != labels) {
+        uint32_t blocks = (n_flows + 2047) / 2048;
+        copy_labels<<<blocks, 256, 0, ctx->stream>>>(pred, labels, n_flows);
+        SF_LAUNCH_CHECK(ctx, "copy_labels");
+    }
 
     sf::Carve ws(ctx);
     const bool bf = mlp->dtype == SF_BF16;

@@ -64,13 +64,13 @@ class GpuRun:
         return u32(self.esc_idx)[:cnt].copy(), cnt
 
     def slow_infer(self, use_raw=False):
-        self.labels.copy_(self.pred)
+        self.labels.fill_(-1)
         if use_raw:
             self.ctx.sf_slow_infer(self.mlp, self.esc_idx, self.esc_count, self.labels, raw_src=self.pk,
                                    raw_pkts=self.cfg.raw_pkts, raw_bits=self.cfg.raw_bits, logits=self.logits,
-                                   esc_cap=self.esc_cap)
+                                   esc_cap=self.esc_cap, pred=self.pred)
         else:
             self.ctx.sf_slow_infer(self.mlp, self.esc_idx, self.esc_count, self.labels, feat=self.feat,
-                                   logits=self.logits, esc_cap=self.esc_cap)
+                                   logits=self.logits, esc_cap=self.esc_cap, pred=self.pred)
         torch.cuda.synchronize()
         return self.logits.cpu().numpy(), u16(self.labels)

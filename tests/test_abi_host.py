@@ -92,7 +92,7 @@ def test_create_rejects_bad_arguments_without_gpu(lib):
     assert lib.sf_featurize(None, None, None, None, 0, None) == -1
     assert lib.sf_fast_infer(None, None, 0, 0, None, None, None, None, None) == -1
     assert lib.sf_route(None, None, None, 0, None, 0, None, None) == -1
-    assert lib.sf_slow_infer(None, None, 0, None, None, None, None, 0, 0, None, None, None) == -1
+    assert lib.sf_slow_infer(None, None, 0, None, None, None, None, 0, 0, None, None, None, None) == -1
 
 
 def test_product_package_never_touches_the_oracle():
