@@ -1,15 +1,20 @@
 // Step 1: per-flow statistics of the first k packets (context length k, Section 3.1 of the
 // paper) and the unpacking of raw header bits (Section 4.1).
 //
-// One lane owns one flow.  Every binary32 operation is issued on its own, in packet order
-// (the file is compiled without floating-point contraction), so the result does not depend
-// on how flows are spread over lanes.  Medians come from stable ranks (the number of
-// elements that sort before an element), which needs no data movement and no sort.
+// One lane owns one flow and keeps its packets in registers.  Every binary32 operation is
+// issued on its own, in packet order (the file is compiled without floating-point
+// contraction), so the result does not depend on how flows are spread over lanes; a packet
+// outside a group contributes +0.0 to that group's running sums, which leaves them unchanged.
+// Order statistics (median, min, max) come from a compare-exchange sorting network over
+// order-preserving integer keys, padded with the largest key; the element at a data-dependent
+// rank is then read through a per-lane column of shared memory.  A block is one wave: its 64
+// feature rows are staged in shared memory per window and written out as full 128-byte runs.
 #include "common.h"
 
 namespace {
 
-constexpr int kLdsLanes = 64; // block size of the long-window variant
+constexpr int kWave = 64;      // flows per block (one wave)
+constexpr int kRow = 33;       // staged row stride in floats (32 + 1 keeps lanes on distinct banks)
 
 struct FeatArgs {
     uint32_t n_flows;
@@ -24,164 +29,137 @@ struct FeatArgs {
     uint32_t ld;
 };
 
-// Packet values of one flow: in registers (short windows) or in a column of shared memory.
-template <int KMAX, bool LDS>
-struct Vals;
-
-template <int KMAX>
-struct Vals<KMAX, false> {
-    float s[KMAX], t[KMAX];
-    __device__ __forceinline__ float S(int j) const { return s[j]; }
-    __device__ __forceinline__ float T(int j) const { return t[j]; }
-};
-
-template <int KMAX>
-struct Vals<KMAX, true> {
-    const float* ps; // [j][lane]
-    const float* pt;
-    __device__ __forceinline__ float S(int j) const { return ps[j * kLdsLanes]; }
-    __device__ __forceinline__ float T(int j) const { return pt[j * kLdsLanes]; }
-};
-
-struct Stat5 {
-    float mean, sd, mn, mx, med;
-};
-
-__device__ __forceinline__ void store32(float* out, const float* f, bool vec)
+// float -> unsigned key with the same order (negative values: all bits flipped, others: sign set)
+__device__ __forceinline__ uint32_t order_key(float x)
 {
-    if (vec) {
+    const uint32_t b = __float_as_uint(x);
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float from_key(uint32_t u)
+{
+    return __uint_as_float(u ^ ((u & 0x80000000u) ? 0x80000000u : 0xFFFFFFFFu));
+}
+
+// Batcher's odd-even merge sort as a fixed network; every index is a compile-time constant
+// after unrolling, so the keys stay in registers.
+template <int N>
+__device__ __forceinline__ void sort_network(uint32_t (&a)[N])
+{
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            reinterpret_cast<float4*>(out)[q] = make_float4(f[4 * q], f[4 * q + 1], f[4 * q + 2], f[4 * q + 3]);
-    } else {
+    for (int p = 1; p < N; p <<= 1) {
 #pragma unroll
-        for (int q = 0; q < 32; ++q) out[q] = f[q];
+        for (int k = p; k >= 1; k >>= 1) {
+#pragma unroll
+            for (int j = k % p; j + k < N; j += 2 * k) {
+#pragma unroll
+                for (int i = 0; i < k; ++i) {
+                    if (i + j + k < N && (i + j) / (2 * p) == (i + j + k) / (2 * p)) {
+                        const uint32_t lo = a[i + j] < a[i + j + k] ? a[i + j] : a[i + j + k];
+                        const uint32_t hi = a[i + j] < a[i + j + k] ? a[i + j + k] : a[i + j];
+                        a[i + j] = lo;
+                        a[i + j + k] = hi;
+                    }
+                }
+            }
+        }
     }
 }
 
-// All 32 statistics of one prefix window of m packets.
-template <int KMAX, bool LDS>
-__device__ __forceinline__ void window_stats(const Vals<KMAX, LDS>& v, uint64_t dmask, int m, float* f)
+__device__ __forceinline__ bool bit_of(uint64_t m, int j) { return (m >> j) & 1ull; }
+
+// Order statistics of one (quantity, group): keys of the group's members, the rest padded.
+template <int N, bool IS_TIME, int KMAX>
+__device__ __forceinline__ void order_stats(const float (&x)[KMAX], uint64_t gm, int cg, uint32_t* col,
+                                            float& mn, float& mx, float& med)
 {
-    const int bound = LDS ? m : KMAX;
-    // ---- pass 1: counts, ordered sums, min, max -------------------------------------------
-    int cnt[3] = {0, 0, 0};
-    float sumS[3] = {0.f, 0.f, 0.f}, sumT[3] = {0.f, 0.f, 0.f};
-    float mnS[3] = {0.f, 0.f, 0.f}, mxS[3] = {0.f, 0.f, 0.f}, mnT[3] = {0.f, 0.f, 0.f}, mxT[3] = {0.f, 0.f, 0.f};
-    float bytes = 0.f;
+    uint32_t key[N];
 #pragma unroll
-    for (int j = 0; j < bound; ++j) {
-        if (j < m) {
-            const float a = v.S(j), b = v.T(j);
-            const int d = (int)((dmask >> j) & 1u);
-            bytes = bytes + a;
-#pragma unroll
-            for (int g = 0; g < 3; ++g) {
-                const bool in = g == 2 || d == g;
-                if (in) {
-                    const bool first = cnt[g] == 0;
-                    sumS[g] = sumS[g] + a;
-                    sumT[g] = sumT[g] + b;
-                    mnS[g] = (first || a < mnS[g]) ? a : mnS[g];
-                    mxS[g] = (first || a > mxS[g]) ? a : mxS[g];
-                    mnT[g] = (first || b < mnT[g]) ? b : mnT[g];
-                    mxT[g] = (first || b > mxT[g]) ? b : mxT[g];
-                    cnt[g] += 1;
-                }
-            }
-        }
+    for (int i = 0; i < N; ++i) {
+        const uint32_t k = IS_TIME ? order_key(x[i]) : (__float_as_uint(x[i]) ^ 0x80000000u); // sizes are >= 0
+        key[i] = bit_of(gm, i) ? k : 0xFFFFFFFFu;
     }
-    float meanS[3], meanT[3];
+    sort_network<N>(key);
 #pragma unroll
+    for (int i = 0; i < N; ++i) col[i * kWave] = key[i];
+    const int last = cg > 0 ? cg - 1 : 0;
+    const uint32_t klo = col[(last >> 1) * kWave], khi = col[(cg >> 1) * kWave], kmx = col[last * kWave];
+    mn = from_key(key[0]);
+    mx = from_key(kmx);
+    const float lo = from_key(klo), hi = from_key(khi);
+    const float two = lo + hi;
+    med = (cg & 1) ? hi : two * 0.5f;
+}
+
+// The 32 statistics of one prefix window of m <= N packets, written to the lane's staged row.
+template <int N, int KMAX>
+__device__ __forceinline__ void window_stats(const float (&s)[KMAX], const float (&t)[KMAX], uint64_t dmask, int m,
+                                             uint32_t* col, float* row)
+{
+    static_assert(N <= KMAX, "window network larger than the register file of the flow");
+    const uint64_t valid = m >= 64 ? ~0ull : ((1ull << m) - 1ull);
+    const uint64_t m1 = dmask & valid, m0 = ~dmask & valid;
+    const int c1 = __popcll(m1), c0 = m - c1;
+    // pass 1: ordered sums
+    float sS0 = 0.f, sS1 = 0.f, sSa = 0.f, sT0 = 0.f, sT1 = 0.f, sTa = 0.f;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const bool v = bit_of(valid, j), d0 = bit_of(m0, j), d1 = bit_of(m1, j);
+        const float a = s[j], b = t[j];
+        sSa = sSa + (v ? a : 0.f);
+        sS0 = sS0 + (d0 ? a : 0.f);
+        sS1 = sS1 + (d1 ? a : 0.f);
+        sTa = sTa + (v ? b : 0.f);
+        sT0 = sT0 + (d0 ? b : 0.f);
+        sT1 = sT1 + (d1 ? b : 0.f);
+    }
+    const float n0 = (float)(c0 > 0 ? c0 : 1), n1 = (float)(c1 > 0 ? c1 : 1), na = (float)(m > 0 ? m : 1);
+    const float mS0 = sS0 / n0, mS1 = sS1 / n1, mSa = sSa / na;
+    const float mT0 = sT0 / n0, mT1 = sT1 / n1, mTa = sTa / na;
+    // pass 2: ordered sums of squared deviations
+    float qS0 = 0.f, qS1 = 0.f, qSa = 0.f, qT0 = 0.f, qT1 = 0.f, qTa = 0.f;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const bool v = bit_of(valid, j), d0 = bit_of(m0, j), d1 = bit_of(m1, j);
+        const float a = s[j], b = t[j];
+        const float ea = a - mSa, eb = b - mTa;
+        const float ea2 = ea * ea, eb2 = eb * eb;
+        qSa = qSa + (v ? ea2 : 0.f);
+        qTa = qTa + (v ? eb2 : 0.f);
+        const float ga = a - (d1 ? mS1 : mS0), gb = b - (d1 ? mT1 : mT0);
+        const float ga2 = ga * ga, gb2 = gb * gb;
+        qS0 = qS0 + (d0 ? ga2 : 0.f);
+        qS1 = qS1 + (d1 ? ga2 : 0.f);
+        qT0 = qT0 + (d0 ? gb2 : 0.f);
+        qT1 = qT1 + (d1 ? gb2 : 0.f);
+    }
+    // per group: assemble the ten statistics (the group index is a run-time loop so that the
+    // sorting network is emitted twice, not six times)
+#pragma unroll 1
     for (int g = 0; g < 3; ++g) {
-        const float c = (float)(cnt[g] > 0 ? cnt[g] : 1);
-        meanS[g] = sumS[g] / c;
-        meanT[g] = sumT[g] / c;
-    }
-    // ---- pass 2: sum of squared deviations, in packet order ------------------------------
-    float ssS[3] = {0.f, 0.f, 0.f}, ssT[3] = {0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < bound; ++j) {
-        if (j < m) {
-            const float a = v.S(j), b = v.T(j);
-            const int d = (int)((dmask >> j) & 1u);
-#pragma unroll
-            for (int g = 0; g < 3; ++g) {
-                const bool in = g == 2 || d == g;
-                if (in) {
-                    const float ta = a - meanS[g];
-                    const float tb = b - meanT[g];
-                    const float qa = ta * ta;
-                    const float qb = tb * tb;
-                    ssS[g] = ssS[g] + qa;
-                    ssT[g] = ssT[g] + qb;
-                }
-            }
-        }
-    }
-    // ---- medians from stable ranks --------------------------------------------------------
-    int tlo[3], thi[3];
-#pragma unroll
-    for (int g = 0; g < 3; ++g) {
-        thi[g] = cnt[g] >> 1;
-        tlo[g] = (cnt[g] - 1) >> 1;
-    }
-    float loS[3] = {0.f, 0.f, 0.f}, hiS[3] = {0.f, 0.f, 0.f}, loT[3] = {0.f, 0.f, 0.f}, hiT[3] = {0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < bound; ++j) {
-        if (j < m) {
-            const float a = v.S(j), b = v.T(j);
-            const int d = (int)((dmask >> j) & 1u);
-            int raS = 0, raT = 0, rgS = 0, rgT = 0;
-#pragma unroll
-            for (int i = 0; i < bound; ++i) {
-                if (i < m && i != j) {
-                    const float ai = v.S(i), bi = v.T(i);
-                    const bool same = (int)((dmask >> i) & 1u) == d;
-                    const bool bS = i < j ? ai <= a : ai < a;
-                    const bool bT = i < j ? bi <= b : bi < b;
-                    raS += bS ? 1 : 0;
-                    raT += bT ? 1 : 0;
-                    rgS += (bS && same) ? 1 : 0;
-                    rgT += (bT && same) ? 1 : 0;
-                }
-            }
-            loS[2] = raS == tlo[2] ? a : loS[2];
-            hiS[2] = raS == thi[2] ? a : hiS[2];
-            loT[2] = raT == tlo[2] ? b : loT[2];
-            hiT[2] = raT == thi[2] ? b : hiT[2];
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const bool in = d == g;
-                loS[g] = (in && rgS == tlo[g]) ? a : loS[g];
-                hiS[g] = (in && rgS == thi[g]) ? a : hiS[g];
-                loT[g] = (in && rgT == tlo[g]) ? b : loT[g];
-                hiT[g] = (in && rgT == thi[g]) ? b : hiT[g];
-            }
-        }
-    }
-    // ---- assemble ------------------------------------------------------------------------
-#pragma unroll
-    for (int g = 0; g < 3; ++g) {
-        const bool empty = cnt[g] == 0;
-        const float c = (float)(empty ? 1 : cnt[g]);
-        const float varS = ssS[g] / c, varT = ssT[g] / c;
-        const bool odd = cnt[g] & 1;
-        const float twoS = loS[g] + hiS[g], twoT = loT[g] + hiT[g];
-        float* o = f + 10 * g;
-        o[0] = empty ? 0.f : meanS[g];
+        const uint64_t gm = g == 0 ? m0 : (g == 1 ? m1 : valid);
+        const int cg = g == 0 ? c0 : (g == 1 ? c1 : m);
+        const float ng = g == 0 ? n0 : (g == 1 ? n1 : na);
+        const float meanS = g == 0 ? mS0 : (g == 1 ? mS1 : mSa), meanT = g == 0 ? mT0 : (g == 1 ? mT1 : mTa);
+        const float ssS = g == 0 ? qS0 : (g == 1 ? qS1 : qSa), ssT = g == 0 ? qT0 : (g == 1 ? qT1 : qTa);
+        const float varS = ssS / ng, varT = ssT / ng;
+        float mnS, mxS, medS, mnT, mxT, medT;
+        order_stats<N, false, KMAX>(s, gm, cg, col, mnS, mxS, medS);
+        order_stats<N, true, KMAX>(t, gm, cg, col, mnT, mxT, medT);
+        const bool empty = cg == 0;
+        float* o = row + 10 * g;
+        o[0] = empty ? 0.f : meanS;
         o[1] = empty ? 0.f : sqrtf(varS);
-        o[2] = empty ? 0.f : mnS[g];
-        o[3] = empty ? 0.f : mxS[g];
-        o[4] = empty ? 0.f : (odd ? hiS[g] : twoS * 0.5f);
-        o[5] = empty ? 0.f : meanT[g];
+        o[2] = empty ? 0.f : mnS;
+        o[3] = empty ? 0.f : mxS;
+        o[4] = empty ? 0.f : medS;
+        o[5] = empty ? 0.f : meanT;
         o[6] = empty ? 0.f : sqrtf(varT);
-        o[7] = empty ? 0.f : mnT[g];
-        o[8] = empty ? 0.f : mxT[g];
-        o[9] = empty ? 0.f : (odd ? hiT[g] : twoT * 0.5f);
+        o[7] = empty ? 0.f : mnT;
+        o[8] = empty ? 0.f : mxT;
+        o[9] = empty ? 0.f : medT;
     }
-    f[30] = bytes;
-    f[31] = (float)m;
+    row[30] = sSa; // total bytes: every partial sum is an integer below 2^24, so this is exact
+    row[31] = (float)m;
 }
 
 __device__ __forceinline__ void flow_range(const FeatArgs& a, uint32_t i, uint32_t& o, uint32_t& n)
@@ -195,15 +173,19 @@ __device__ __forceinline__ void flow_range(const FeatArgs& a, uint32_t i, uint32
 }
 
 template <int KMAX>
-__global__ __launch_bounds__(256) void featurize_reg(FeatArgs a)
+__global__ __launch_bounds__(kWave) void featurize_wave(FeatArgs a)
 {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= a.n_flows) return;
-    uint32_t o, n;
-    flow_range(a, i, o, n);
+    __shared__ uint32_t sort_col[KMAX * kWave]; // [rank][lane]
+    __shared__ float tile[kWave * kRow];        // [lane][33]
+    const uint32_t lane = threadIdx.x;
+    const uint32_t tile0 = blockIdx.x * kWave;
+    const uint32_t i = tile0 + lane;
+    const bool live = i < a.n_flows;
+    uint32_t o = 0, n = 0;
+    if (live) flow_range(a, i, o, n);
     const uint32_t dmax = a.depth[a.n_windows - 1];
     const int avail = (int)(n < dmax ? n : dmax);
-    Vals<KMAX, false> v;
+    float s[KMAX], t[KMAX];
     uint64_t dmask = 0;
     if (avail == KMAX && (o & 7u) == 0) {
         // whole window present and 16-byte aligned: wide loads
@@ -213,13 +195,13 @@ __global__ __launch_bounds__(256) void featurize_reg(FeatArgs a)
             const uint32_t w[4] = {sz.x, sz.y, sz.z, sz.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                v.s[8 * c + 2 * k] = (float)(w[k] & 0xFFFFu);
-                v.s[8 * c + 2 * k + 1] = (float)(w[k] >> 16);
+                s[8 * c + 2 * k] = (float)(w[k] & 0xFFFFu);
+                s[8 * c + 2 * k + 1] = (float)(w[k] >> 16);
             }
             const float4 t0 = *reinterpret_cast<const float4*>(a.iat + o + 8 * c);
             const float4 t1 = *reinterpret_cast<const float4*>(a.iat + o + 8 * c + 4);
-            v.t[8 * c + 0] = t0.x; v.t[8 * c + 1] = t0.y; v.t[8 * c + 2] = t0.z; v.t[8 * c + 3] = t0.w;
-            v.t[8 * c + 4] = t1.x; v.t[8 * c + 5] = t1.y; v.t[8 * c + 6] = t1.z; v.t[8 * c + 7] = t1.w;
+            t[8 * c + 0] = t0.x; t[8 * c + 1] = t0.y; t[8 * c + 2] = t0.z; t[8 * c + 3] = t0.w;
+            t[8 * c + 4] = t1.x; t[8 * c + 5] = t1.y; t[8 * c + 6] = t1.z; t[8 * c + 7] = t1.w;
             const uint2 dd = *reinterpret_cast<const uint2*>(a.dir + o + 8 * c);
             const uint32_t dw[2] = {dd.x, dd.y};
 #pragma unroll
@@ -230,56 +212,37 @@ __global__ __launch_bounds__(256) void featurize_reg(FeatArgs a)
 #pragma unroll
         for (int j = 0; j < KMAX; ++j) {
             if (j < avail) {
-                v.s[j] = (float)a.size[o + j];
-                v.t[j] = a.iat[o + j];
+                s[j] = (float)a.size[o + j];
+                t[j] = a.iat[o + j];
                 dmask |= (uint64_t)(a.dir[o + j] & 1u) << j;
             } else {
-                v.s[j] = 0.f;
-                v.t[j] = 0.f;
+                s[j] = 0.f;
+                t[j] = 0.f;
             }
         }
     }
-    float* out = a.feat + (size_t)i * a.ld;
-    const bool vec = (a.ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0;
-#pragma unroll
-    for (int w = 0; w < SF_MAX_WINDOWS; ++w) {
-        if (w < (int)a.n_windows) {
-            const int m = avail < (int)a.depth[w] ? avail : (int)a.depth[w];
-            float f[32];
-            window_stats<KMAX, false>(v, dmask, m, f);
-            store32(out + 32 * w, f, vec);
-        }
-    }
-}
-
-// Long windows (up to 64 packets): the flow's values sit in a column of shared memory,
-// [packet][lane], so that lane l always hits bank l % 32.
-__global__ __launch_bounds__(kLdsLanes) void featurize_lds(FeatArgs a)
-{
-    __shared__ float ls[SF_MAX_DEPTH_PKTS * kLdsLanes];
-    __shared__ float lt[SF_MAX_DEPTH_PKTS * kLdsLanes];
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= a.n_flows) return;
-    uint32_t o, n;
-    flow_range(a, i, o, n);
-    const uint32_t dmax = a.depth[a.n_windows - 1];
-    const int avail = (int)(n < dmax ? n : dmax);
-    uint64_t dmask = 0;
-    float* cs = ls + threadIdx.x;
-    float* ct = lt + threadIdx.x;
-    for (int j = 0; j < avail; ++j) {
-        cs[j * kLdsLanes] = (float)a.size[o + j];
-        ct[j * kLdsLanes] = a.iat[o + j];
-        dmask |= (uint64_t)(a.dir[o + j] & 1u) << j;
-    }
-    Vals<SF_MAX_DEPTH_PKTS, true> v{cs, ct};
-    float* out = a.feat + (size_t)i * a.ld;
-    const bool vec = (a.ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0;
-    for (int w = 0; w < (int)a.n_windows; ++w) {
-        const int m = avail < (int)a.depth[w] ? avail : (int)a.depth[w];
-        float f[32];
-        window_stats<SF_MAX_DEPTH_PKTS, true>(v, dmask, m, f);
-        store32(out + 32 * w, f, vec);
+    uint32_t* col = sort_col + lane;
+    float* row = tile + lane * kRow;
+    uint32_t rows = a.n_flows - tile0;
+    rows = rows < (uint32_t)kWave ? rows : (uint32_t)kWave;
+    for (uint32_t w = 0; w < a.n_windows; ++w) {
+        const int dw = (int)a.depth[w];
+        const int m = avail < dw ? avail : dw;
+        // the smallest network that covers every lane's window (wave-uniform choice)
+        if (KMAX >= 64 && __any(m > 32))
+            window_stats<(KMAX >= 64 ? 64 : KMAX), KMAX>(s, t, dmask, m, col, row);
+        else if (KMAX >= 32 && __any(m > 16))
+            window_stats<(KMAX >= 32 ? 32 : KMAX), KMAX>(s, t, dmask, m, col, row);
+        else if (KMAX >= 16 && __any(m > 8))
+            window_stats<(KMAX >= 16 ? 16 : KMAX), KMAX>(s, t, dmask, m, col, row);
+        else
+            window_stats<8, KMAX>(s, t, dmask, m, col, row);
+        __syncthreads();
+        // half a wave writes one staged row: 32 consecutive floats = one 128-byte run
+        const uint32_t c = lane & 31u, half = lane >> 5;
+        for (uint32_t r = half; r < rows; r += 2)
+            a.feat[(size_t)(tile0 + r) * a.ld + 32u * w + c] = tile[r * kRow + c];
+        __syncthreads();
     }
 }
 
@@ -353,16 +316,15 @@ extern "C" int sf_featurize(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg
     a.feat = feat;
     a.ld = feat_ld;
     const uint32_t dmax = cfg->depth[cfg->n_windows - 1];
-    if (dmax <= 16) {
-        const uint32_t bs = 256, grid = (a.n_flows + bs - 1) / bs;
-        if (dmax <= 8)
-            featurize_reg<8><<<grid, bs, 0, ctx->stream>>>(a);
-        else
-            featurize_reg<16><<<grid, bs, 0, ctx->stream>>>(a);
-    } else {
-        const uint32_t grid = (a.n_flows + kLdsLanes - 1) / kLdsLanes;
-        featurize_lds<<<grid, kLdsLanes, 0, ctx->stream>>>(a);
-    }
+    const uint32_t grid = (a.n_flows + kWave - 1) / kWave;
+    if (dmax <= 8)
+        featurize_wave<8><<<grid, kWave, 0, ctx->stream>>>(a);
+    else if (dmax <= 16)
+        featurize_wave<16><<<grid, kWave, 0, ctx->stream>>>(a);
+    else if (dmax <= 32)
+        featurize_wave<32><<<grid, kWave, 0, ctx->stream>>>(a);
+    else
+        featurize_wave<64><<<grid, kWave, 0, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "featurize");
     if (raw) {
         const uint64_t total = (uint64_t)a.n_flows * cfg->raw_pkts * ((cfg->raw_bits + 31) / 32);
