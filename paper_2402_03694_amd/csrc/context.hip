@@ -29,12 +29,6 @@ int fail(sf_ctx* ctx, int code, const char* fmt, ...)
     return code;
 }
 
-size_t forest_pack_bytes(uint32_t n_trees, uint32_t depth)
-{
-    if (n_trees == 0 || depth == 0 || depth > SF_MAX_TREE_DEPTH) return 0;
-    return align_up((size_t)n_trees * ((size_t)1 << depth) * 8);
-}
-
 size_t route_scratch_bytes(uint32_t n_flows)
 {
     (void)n_flows;

@@ -3,49 +3,56 @@
 // Section 3.2 (top_votes = max_y votes[y]; LC = 1 - top_votes / n_trees).
 //
 // Work split: one lane owns one flow.  Its feature row sits in shared memory as a column,
-// [feature][lane], so the data-dependent feature fetch x[feat] of every lane of a wave lands
-// in its own bank.  Nodes are re-packed once per call to 8 bytes (threshold, feature index
-// and, on the last level, the two leaf labels), so that one 8-byte load serves one visit and
-// no separate leaf-label fetch is needed.  Several trees are walked at once per lane to keep
+// [feature][lane], so the data-dependent fetch x[feat] of every lane of a wave lands in its own
+// bank.  What bounds the walk is the number of vector-memory instructions (a compute unit
+// retires a 64-lane gather roughly every 16 cycles whatever it hits), so the forest is re-packed
+// once per call into 16-byte records that hold TWO levels: a node and both its children (three
+// thresholds, three feature indices).  One 16-byte load then serves two visits.  Records form a
+// quaternary heap per tree (record r has children 4r+1..4r+4); the records of the top levels of
+// every tree are staged in shared memory, the deeper ones come through the cache; the leaf
+// label is one byte load at the end.  Several trees are walked at once per lane to keep
 // independent loads in flight.  Votes are integers in shared memory; nothing here rounds.
 #include "common.h"
 
 namespace {
 
-struct __align__(8) PackedNode {
-    float thr;
-    uint32_t meta; // bits 0..15 feature; last level: bits 16..23 left label, 24..31 right label
+struct __align__(16) PairRec {
+    float thr0, thr1, thr2; // node, its left child, its right child
+    uint32_t feats;         // bits 0..7, 8..15, 16..23: their feature indices
 };
 
+__host__ __device__ inline uint32_t pair_levels(uint32_t depth) { return (depth + 1u) / 2u; }
+__host__ __device__ inline uint32_t recs_upto(uint32_t j) { return ((1u << (2u * j)) - 1u) / 3u; } // (4^j-1)/3
+
 __global__ __launch_bounds__(256) void pack_forest(uint32_t n_trees, uint32_t depth, uint32_t n_features,
-                                                   uint32_t n_classes, const uint16_t* __restrict__ nf,
-                                                   const float* __restrict__ nt, const uint8_t* __restrict__ ll,
-                                                   PackedNode* __restrict__ out)
+                                                   const uint16_t* __restrict__ nf, const float* __restrict__ nt,
+                                                   PairRec* __restrict__ out)
 {
-    const uint32_t n_int = (1u << depth) - 1u, stride = 1u << depth;
-    const uint64_t total = (uint64_t)n_trees * stride;
+    const uint32_t n_int = (1u << depth) - 1u;
+    const uint32_t n_rec = recs_upto(pair_levels(depth));
+    const uint64_t total = (uint64_t)n_trees * n_rec;
     for (uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total;
          g += (uint64_t)gridDim.x * blockDim.x) {
-        const uint32_t t = (uint32_t)(g >> depth), k = (uint32_t)(g & (stride - 1));
-        PackedNode p;
-        if (k < n_int) {
-            uint32_t f = nf[(size_t)t * n_int + k];
-            f = f < n_features ? f : n_features - 1; // clamp: a bad index must not leave the row
-            uint32_t meta = f;
-            const uint32_t first_last = (1u << (depth - 1)) - 1u;
-            if (k >= first_last) {
-                const uint32_t leaf = 2 * (k - first_last);
-                uint32_t l0 = ll[(size_t)t * stride + leaf], l1 = ll[(size_t)t * stride + leaf + 1];
-                l0 = l0 < n_classes ? l0 : n_classes - 1;
-                l1 = l1 < n_classes ? l1 : n_classes - 1;
-                meta |= (l0 << 16) | (l1 << 24);
-            }
-            p.thr = nt[(size_t)t * n_int + k];
-            p.meta = meta;
-        } else {
-            p.thr = 0.f;
-            p.meta = 0;
+        const uint32_t t = (uint32_t)(g / n_rec), r = (uint32_t)(g % n_rec);
+        uint32_t j = 0;
+        while (recs_upto(j + 1) <= r) ++j;                 // pair-level of record r
+        const uint32_t pos = r - recs_upto(j);             // position within tree level 2j
+        const uint32_t k0 = ((1u << (2u * j)) - 1u) + pos; // heap index of the record's top node
+        const uint32_t ks[3] = {k0, 2u * k0 + 1u, 2u * k0 + 2u};
+        float thr[3];
+        uint32_t fe[3];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            const bool have = ks[q] < n_int;               // odd depth: the last records have no children
+            uint32_t f = have ? nf[(size_t)t * n_int + ks[q]] : 0u;
+            fe[q] = f < n_features ? f : n_features - 1u;  // clamp: a bad index must not leave the row
+            thr[q] = have ? nt[(size_t)t * n_int + ks[q]] : 0.f;
         }
+        PairRec p;
+        p.thr0 = thr[0];
+        p.thr1 = thr[1];
+        p.thr2 = thr[2];
+        p.feats = fe[0] | (fe[1] << 8) | (fe[2] << 16);
         out[g] = p;
     }
 }
@@ -55,27 +62,39 @@ struct FastArgs {
     uint32_t ld;
     uint32_t n_flows;
     uint32_t n_trees, depth, n_classes, n_features;
-    const PackedNode* nodes;
+    uint32_t top_pairs; // pair-levels of every tree staged in shared memory
+    uint32_t vote_bits; // width of one packed vote counter: 8 (n_trees <= 255) or 16
+    const PairRec* recs;
+    const uint8_t* leaf_label;
     uint16_t* votes;
     uint16_t* pred;
     uint16_t* top;
     uint16_t* leaf_idx;
 };
 
-constexpr int kIlp = 4; // trees walked at once per lane
+#ifndef SF_FAST_ILP
+#define SF_FAST_ILP 8
+#endif
+constexpr int kIlp = SF_FAST_ILP; // trees walked at once per lane
 
 template <int BS, bool WANT_LEAF>
 __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
 {
-    extern __shared__ float smem[];
-    float* xT = smem;                                                     // [n_features][BS]
-    uint32_t* vT = reinterpret_cast<uint32_t*>(smem + (size_t)a.n_features * BS); // [n_classes][BS]
+    constexpr uint32_t kColShift = BS == 256 ? 10 : (BS == 128 ? 9 : 8); // log2(bytes per feature column)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const uint32_t F = a.n_features, C = a.n_classes, T = a.n_trees;
+    const uint32_t top_recs = recs_upto(a.top_pairs);      // records per tree held in shared memory
+    float* xT = reinterpret_cast<float*>(smem_raw);                          // [F][BS]
+    // vote counters, 32 / vote_bits classes per word: [ceil(C * vote_bits / 32)][BS]
+    const uint32_t per_shift = a.vote_bits == 8 ? 2u : 1u; // log2(counters per word)
+    const uint32_t vote_words = (C + (1u << per_shift) - 1u) >> per_shift;
+    uint32_t* vT = reinterpret_cast<uint32_t*>(xT + (size_t)F * BS);
+    uint4* topT = reinterpret_cast<uint4*>(vT + (size_t)vote_words * BS);    // [T][top_recs]
     const uint32_t tid = threadIdx.x;
     const uint32_t i = blockIdx.x * BS + tid;
     const bool live = i < a.n_flows;
     const uint32_t row = live ? i : a.n_flows - 1; // idle lanes walk a valid row, write nothing
     const float* x = a.feat + (size_t)row * a.ld;
-    const uint32_t F = a.n_features;
     if ((a.ld & 3u) == 0 && (F & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0) {
         for (uint32_t q = 0; q < F / 4; ++q) {
             const float4 v = reinterpret_cast<const float4*>(x)[q];
@@ -87,57 +106,102 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     } else {
         for (uint32_t f = 0; f < F; ++f) xT[f * BS + tid] = x[f];
     }
-    for (uint32_t c = 0; c < a.n_classes; ++c) vT[c * BS + tid] = 0;
-    // each lane reads back only what it wrote itself: no barrier needed
+    for (uint32_t c = 0; c < vote_words; ++c) vT[c * BS + tid] = 0;
+    const uint32_t n_rec = recs_upto(pair_levels(a.depth));
+    const uint4* recs = reinterpret_cast<const uint4*>(a.recs);
+    for (uint32_t q = tid; q < T * top_recs; q += BS) {
+        const uint32_t t = q / top_recs, r = q - t * top_recs;
+        topT[q] = recs[(size_t)t * n_rec + r];
+    }
+    __syncthreads(); // the staged records are shared by the block
 
     const uint32_t depth = a.depth;
-    const uint32_t stride = 1u << depth;
-    const uint32_t n_int = stride - 1u;
-    const float* xcol = xT + tid;
+    const uint32_t full_pairs = depth >> 1;
+    const uint32_t lds_pairs = a.top_pairs < full_pairs ? a.top_pairs : full_pairs;
+    const bool odd = depth & 1u;
+    const char* xlane = reinterpret_cast<const char*>(xT) + tid * 4u; // the lane's column
     uint32_t* vcol = vT + tid;
-    uint32_t t = 0;
-    for (; t + kIlp <= a.n_trees; t += kIlp) {
-        uint32_t k[kIlp];
-        uint32_t lab[kIlp];
-#pragma unroll
-        for (int u = 0; u < kIlp; ++u) k[u] = 0;
-        for (uint32_t lvl = 0; lvl < depth; ++lvl) {
-            PackedNode nd[kIlp];
-#pragma unroll
-            for (int u = 0; u < kIlp; ++u) nd[u] = a.nodes[(size_t)(t + u) * stride + k[u]];
-#pragma unroll
-            for (int u = 0; u < kIlp; ++u) {
-                const float xv = xcol[(nd[u].meta & 0xFFFFu) * BS];
-                const bool left = xv <= nd[u].thr;
-                k[u] = 2 * k[u] + (left ? 1u : 2u);
-                lab[u] = left ? (nd[u].meta >> 16) & 0xFFu : nd[u].meta >> 24;
-            }
-        }
+    const uint32_t rec_bytes = n_rec * 16u, top_bytes = top_recs * 16u;
+    const uint32_t leaf_base = recs_upto(full_pairs); // record index of position 0 on tree level 2*full_pairs
+    const uint32_t n_leaf = 1u << depth;
+
+    // two visits from one record; o is the byte offset of the record inside its tree
+#define SF_PAIR_STEP(REC, O)                                                                              \
+    do {                                                                                                  \
+        const uint32_t fw = (REC).w;                                                                      \
+        const float x0 = *reinterpret_cast<const float*>(xlane + ((fw & 0xFFu) << kColShift));            \
+        const float x1 = *reinterpret_cast<const float*>(xlane + (((fw >> 8) & 0xFFu) << kColShift));     \
+        const float x2 = *reinterpret_cast<const float*>(xlane + ((fw >> 16) << kColShift));              \
+        const bool r0 = !(x0 <= __uint_as_float((REC).x));                                                \
+        const bool r1 = !(x1 <= __uint_as_float((REC).y));                                                \
+        const bool r2 = !(x2 <= __uint_as_float((REC).z));                                                \
+        const uint32_t inc_l = r1 ? 32u : 16u, inc_r = r2 ? 64u : 48u;                                    \
+        (O) = 4u * (O) + (r0 ? inc_r : inc_l);                                                            \
+    } while (0)
+
+    for (uint32_t t0 = 0; t0 < T; t0 += kIlp) {
+        uint32_t o[kIlp], tt[kIlp];
 #pragma unroll
         for (int u = 0; u < kIlp; ++u) {
-            vcol[lab[u] * BS] += 1;
-            if (WANT_LEAF && live) a.leaf_idx[(size_t)i * a.n_trees + t + u] = (uint16_t)(k[u] - n_int);
+            o[u] = 0;
+            tt[u] = t0 + u < T ? t0 + u : T - 1; // the tail repeats the last tree and does not vote
+        }
+        uint32_t j = 0;
+        for (; j < lds_pairs; ++j) {
+            uint4 rec[kIlp];
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u)
+                rec[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(topT) + tt[u] * top_bytes + o[u]);
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u) SF_PAIR_STEP(rec[u], o[u]);
+        }
+        const char* gb = reinterpret_cast<const char*>(a.recs);
+        for (; j < full_pairs; ++j) {
+            uint4 rec[kIlp];
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u)
+                rec[u] = *reinterpret_cast<const uint4*>(gb + (size_t)tt[u] * rec_bytes + o[u]);
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u) SF_PAIR_STEP(rec[u], o[u]);
+        }
+        uint32_t leaf[kIlp];
+        if (odd) {
+            // one level left: only the record's top node counts
+            uint4 rec[kIlp];
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u)
+                rec[u] = *reinterpret_cast<const uint4*>(gb + (size_t)tt[u] * rec_bytes + o[u]);
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u) {
+                const float x0 = *reinterpret_cast<const float*>(xlane + ((rec[u].w & 0xFFu) << kColShift));
+                const bool r0 = !(x0 <= __uint_as_float(rec[u].x));
+                leaf[u] = 2u * ((o[u] >> 4) - leaf_base) + (r0 ? 1u : 0u);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u) leaf[u] = (o[u] >> 4) - leaf_base;
+        }
+        uint32_t lab[kIlp];
+#pragma unroll
+        for (int u = 0; u < kIlp; ++u) lab[u] = a.leaf_label[(size_t)tt[u] * n_leaf + leaf[u]];
+#pragma unroll
+        for (int u = 0; u < kIlp; ++u) {
+            if (t0 + u < T) {
+                const uint32_t l = lab[u] < C ? lab[u] : C - 1u; // clamp: a bad label must not leave the tile
+                // only this lane touches its column; the add is one shared-memory instruction
+                atomicAdd(&vcol[(l >> per_shift) * BS], 1u << ((l & ((1u << per_shift) - 1u)) * a.vote_bits));
+                if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + t0 + u] = (uint16_t)leaf[u];
+            }
         }
     }
-    for (; t < a.n_trees; ++t) {
-        uint32_t k = 0, lab = 0;
-        for (uint32_t lvl = 0; lvl < depth; ++lvl) {
-            const PackedNode nd = a.nodes[(size_t)t * stride + k];
-            const float xv = xcol[(nd.meta & 0xFFFFu) * BS];
-            const bool left = xv <= nd.thr;
-            k = 2 * k + (left ? 1u : 2u);
-            lab = left ? (nd.meta >> 16) & 0xFFu : nd.meta >> 24;
-        }
-        vcol[lab * BS] += 1;
-        if (WANT_LEAF && live) a.leaf_idx[(size_t)i * a.n_trees + t] = (uint16_t)(k - n_int);
-    }
+#undef SF_PAIR_STEP
     if (!live) return;
-    uint32_t best = 0, bestv = vcol[0];
-    if (a.votes) a.votes[(size_t)i * a.n_classes] = (uint16_t)bestv;
-    for (uint32_t c = 1; c < a.n_classes; ++c) {
-        const uint32_t v = vcol[c * BS];
-        if (a.votes) a.votes[(size_t)i * a.n_classes + c] = (uint16_t)v;
-        if (v > bestv) {
+    uint32_t best = 0, bestv = 0;
+    const uint32_t vmask = (1u << a.vote_bits) - 1u;
+    for (uint32_t c = 0; c < C; ++c) {
+        const uint32_t v = (vcol[(c >> per_shift) * BS] >> ((c & ((1u << per_shift) - 1u)) * a.vote_bits)) & vmask;
+        if (a.votes) a.votes[(size_t)i * C + c] = (uint16_t)v;
+        if (c == 0 || v > bestv) {
             bestv = v;
             best = c;
         }
@@ -165,6 +229,14 @@ int launch_votes(sf_ctx* ctx, const FastArgs& a, size_t lds)
 
 } // namespace
 
+namespace sf {
+size_t forest_pack_bytes(uint32_t n_trees, uint32_t depth)
+{
+    if (n_trees == 0 || depth == 0 || depth > SF_MAX_TREE_DEPTH) return 0;
+    return align_up((size_t)n_trees * recs_upto(pair_levels(depth)) * sizeof(PairRec));
+}
+} // namespace sf
+
 extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
                              const sf_forest* forest, uint16_t* votes, uint16_t* pred, uint16_t* top_votes,
                              uint16_t* leaf_idx)
@@ -189,17 +261,16 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
 
     sf::Carve ws(ctx);
     const size_t pack_bytes = sf::forest_pack_bytes(forest->n_trees, forest->depth);
-    PackedNode* packed = (PackedNode*)ws.take(pack_bytes);
+    PairRec* packed = (PairRec*)ws.take(pack_bytes);
     if (!packed)
         return sf::fail(ctx, SF_ENOMEM, "sf_fast_infer: workspace has %zu bytes, packed forest needs %zu",
                         ctx->ws_bytes, pack_bytes + sf::kFlagBytes);
     {
-        const uint64_t total = (uint64_t)forest->n_trees << forest->depth;
+        const uint64_t total = (uint64_t)forest->n_trees * recs_upto(pair_levels(forest->depth));
         uint64_t blocks = (total + 255) / 256;
         if (blocks > 8192) blocks = 8192;
         pack_forest<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(forest->n_trees, forest->depth, forest->n_features,
-                                                               forest->n_classes, forest->node_feat, forest->node_thr,
-                                                               forest->leaf_label, packed);
+                                                               forest->node_feat, forest->node_thr, packed);
         SF_LAUNCH_CHECK(ctx, "pack_forest");
     }
     FastArgs a;
@@ -210,14 +281,33 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     a.depth = forest->depth;
     a.n_classes = forest->n_classes;
     a.n_features = forest->n_features;
-    a.nodes = packed;
+    a.recs = packed;
+    a.leaf_label = forest->leaf_label;
     a.votes = votes;
     a.pred = pred;
     a.top = top_votes;
     a.leaf_idx = leaf_idx;
-    // bytes of shared memory per lane; two blocks per compute unit when they fit in 160 KB
-    const size_t per_lane = ((size_t)a.n_features + a.n_classes) * 4;
-    if (per_lane * 256 <= 80 * 1024) return launch_votes<256>(ctx, a, per_lane * 256);
-    if (per_lane * 128 <= 80 * 1024) return launch_votes<128>(ctx, a, per_lane * 128);
-    return launch_votes<64>(ctx, a, per_lane * 64);
+    // Shared memory per block: a feature column and packed vote counters per lane, plus the staged
+    // top records of every tree.  Two blocks per compute unit (160 KB) keep eight waves resident;
+    // what is left of a block's half goes to the top records.
+    a.vote_bits = a.n_trees <= 255 ? 8u : 16u;
+    const uint32_t vote_words = (a.n_classes * a.vote_bits + 31u) / 32u;
+    const size_t per_lane = ((size_t)a.n_features + vote_words) * 4;
+    const size_t budget = 80 * 1024 - 512;
+    const uint32_t bs = per_lane * 256 <= budget ? 256u : (per_lane * 128 <= budget ? 128u : 64u);
+    const uint32_t full_pairs = forest->depth / 2;
+    uint32_t top_pairs = 0;
+#ifdef SF_FAST_TOP_PAIRS
+    const uint32_t want_pairs = SF_FAST_TOP_PAIRS;
+#else
+    const uint32_t want_pairs = 8;
+#endif
+    while (top_pairs < full_pairs && top_pairs < want_pairs &&
+           per_lane * bs + (size_t)a.n_trees * recs_upto(top_pairs + 1) * 16 <= budget)
+        ++top_pairs;
+    a.top_pairs = top_pairs;
+    const size_t lds = per_lane * bs + (size_t)a.n_trees * recs_upto(top_pairs) * 16;
+    if (bs == 256) return launch_votes<256>(ctx, a, lds);
+    if (bs == 128) return launch_votes<128>(ctx, a, lds);
+    return launch_votes<64>(ctx, a, lds);
 }
