@@ -1,0 +1,371 @@
+// Step 5, fused form for hidden widths up to 512: the whole 3-layer MLP of a tile of 128
+// escalated flows runs in one block without touching HBM between layers (Sections 3.1 and 4.4
+// of the paper: only the uncertain flows reach the slow model, and its label replaces the fast
+// one).
+//
+// A block is eight waves; wave w owns output columns [64w, 64w+64) of each hidden layer for
+// all 128 rows, i.e. a 4x2 grid of 32x32 MFMA accumulators (128 accumulator registers).  The
+// activations of the tile stay in shared memory ([128][520] bfloat16, 16-byte reads of 8
+// consecutive rows fall on distinct banks); the weights are re-ordered once per call so that
+// the 8 K-values a lane needs for an MFMA B operand are contiguous and a wave's operand is one
+// contiguous kilobyte, and are then read straight from the cache into registers.  There is no
+// barrier inside a layer's K loop.  The last layer (at most 32 classes) is one 32x32 block for
+// each of four waves, followed by a per-row arg-max in registers and the scatter of the label.
+// Blocks are persistent: each walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... up to the
+// device-side escalation count, so no block is launched for rows that do not exist.
+#include "common.h"
+
+namespace sf {
+bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
+size_t slow_fused_ws_bytes(const sf_mlp* mlp);
+int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
+               const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* mlp, float* logits, uint16_t* labels);
+} // namespace sf
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int FBM = 128;      // rows per tile
+constexpr int HMAX = 512;     // widest hidden layer
+constexpr int LDH = HMAX + 8; // activation row stride in elements
+
+__host__ __device__ inline uint32_t up(uint32_t x, uint32_t m) { return (x + m - 1u) / m * m; }
+
+struct FusedArgs {
+    const uint32_t* esc_idx;
+    const uint32_t* esc_count;
+    uint32_t esc_cap;
+    const float* feat;
+    uint32_t feat_ld;
+    const float* mu;
+    const float* inv_sigma;
+    float clamp;
+    uint32_t n_in, h1, h2, c;
+    const uint4* w1s; // operand-ordered weights, see reorder_weights
+    const uint4* w2s;
+    const uint4* w3s;
+    const float *b1, *b2, *b3;
+    float* logits;
+    uint16_t* labels;
+};
+
+__device__ __forceinline__ uint16_t to_bf16_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);
+    u += 0x7FFFu + ((u >> 16) & 1u); // round to nearest even
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ bf16x8 as_frag(uint4 u)
+{
+    union {
+        uint4 u;
+        bf16x8 b;
+    } c;
+    c.u = u;
+    return c.b;
+}
+
+// W[N][K] (row-major, bfloat16 bits) -> out[(nb * KS + ks) * 64 + lane] = the 8 values
+// W[nb*32 + lane%32][ks*16 + 8*(lane/32) .. +8), zero outside; nb < NB, ks < KS.
+__global__ __launch_bounds__(256) void reorder_weights(const uint16_t* __restrict__ w, uint32_t N, uint32_t K, uint32_t NB,
+                                                       uint32_t KS, uint4* __restrict__ out)
+{
+    const uint32_t total = NB * KS * 64u;
+    for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < total; g += gridDim.x * blockDim.x) {
+        const uint32_t lane = g & 63u, t = g >> 6, ks = t % KS, nb = t / KS;
+        const uint32_t n = nb * 32u + (lane & 31u), k0 = ks * 16u + 8u * (lane >> 5);
+        uint16_t v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = (n < N && k0 + q < K) ? w[(size_t)n * K + k0 + q] : (uint16_t)0;
+        out[g] = make_uint4(v[0] | ((uint32_t)v[1] << 16), v[2] | ((uint32_t)v[3] << 16), v[4] | ((uint32_t)v[5] << 16),
+                            v[6] | ((uint32_t)v[7] << 16));
+    }
+}
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// two floats -> two bfloat16 (round to nearest even) in one word
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    union {
+        bf16x2 b;
+        uint32_t u;
+    } c;
+    c.b = __builtin_convertvector(v, bf16x2);
+    return c.u;
+}
+
+constexpr int kWaves = 8;  // waves per block
+constexpr int kNI = 2;     // 32-column blocks per wave (64 columns)
+constexpr int kMI = 4;     // 32-row blocks per wave (all 128 rows)
+constexpr int kAhead = 2;  // k-steps of weight operands in flight
+
+// The MFMA is issued with the WEIGHT operand first, so the 32x32 accumulator block holds the
+// output transposed: element v of lane l is output column 8*(v/4) + 4*(l/32) + v%4 of
+// activation row l%32.  Four consecutive v are four consecutive columns of one row, which lets
+// the epilogue write 8 bytes at a time.
+// acc[i][j] += W[cols of block nb0+j][K] * A[rows 32i..32i+32)[K]^T
+__device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const uint4* __restrict__ ws, uint32_t KS,
+                                          uint32_t nb0, uint32_t nb_cnt, uint32_t lane, f32x16 (&acc)[kMI][kNI])
+{
+    if (nb_cnt == 0) return;
+    const uint16_t* arow = A + (lane & 31u) * lda + 8u * (lane >> 5);
+    const uint4* wl = ws + (size_t)nb0 * KS * 64u + lane;
+    uint4 fb[kAhead][kNI];
+#pragma unroll
+    for (int s = 0; s < kAhead; ++s)
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) {
+            const uint32_t kk = (uint32_t)s < KS ? (uint32_t)s : KS - 1u;
+            fb[s][j] = (uint32_t)j < nb_cnt ? wl[((size_t)j * KS + kk) * 64u] : make_uint4(0, 0, 0, 0);
+        }
+    for (uint32_t ks = 0; ks < KS; ++ks) {
+        uint4 nx[kNI];
+        const uint32_t kn = ks + kAhead < KS ? ks + kAhead : KS - 1u;
+#pragma unroll
+        for (int j = 0; j < kNI; ++j)
+            nx[j] = (uint32_t)j < nb_cnt ? wl[((size_t)j * KS + kn) * 64u] : make_uint4(0, 0, 0, 0);
+        bf16x8 fa[kMI];
+#pragma unroll
+        for (int i = 0; i < kMI; ++i) fa[i] = as_frag(*reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda + ks * 16u));
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) {
+            const bf16x8 b = as_frag(fb[0][j]);
+#pragma unroll
+            for (int i = 0; i < kMI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[i], acc[i][j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) {
+#pragma unroll
+            for (int s = 0; s + 1 < kAhead; ++s) fb[s][j] = fb[s + 1][j];
+            fb[kAhead - 1][j] = nx[j];
+        }
+    }
+}
+
+// H[row][col] = bfloat16(relu(acc + bias)) for the wave's columns; columns in [n_valid, n_pad) become zeros
+__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], const float* __restrict__ bias,
+                                             uint32_t n0, uint32_t n_valid, uint32_t n_pad, uint32_t lane)
+{
+#pragma unroll
+    for (int j = 0; j < kNI; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5); // first of 4 consecutive columns
+            if (col < n_pad) {
+                float b[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) b[q] = col + q < n_valid ? bias[col + q] : 0.f;
+#pragma unroll
+                for (int i = 0; i < kMI; ++i) {
+                    const uint32_t row = i * 32u + (lane & 31u);
+                    float y[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        y[q] = acc[i][j][4 * g + q] + b[q];
+                        y[q] = y[q] > 0.f ? y[q] : 0.f;
+                        y[q] = col + q < n_valid ? y[q] : 0.f;
+                    }
+                    *reinterpret_cast<uint2*>(H + row * LDH + col) = make_uint2(pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3]));
+                }
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[kMI][kNI])
+{
+#pragma unroll
+    for (int i = 0; i < kMI; ++i)
+#pragma unroll
+        for (int j = 0; j < kNI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+}
+
+__global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* H = reinterpret_cast<uint16_t*>(smem);                            // [128][LDH]; also the input tile
+    uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)FBM * LDH * 2); // [128]
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    uint32_t total = *a.esc_count;
+    total = total < a.esc_cap ? total : a.esc_cap;
+    const uint32_t n_tiles = (total + FBM - 1) / FBM;
+    const uint32_t k1p = up(a.n_in, 16), k2p = up(a.h1, 16), k3p = up(a.h2, 16);
+    const uint32_t ldx = k1p + 8; // input tile row stride
+    const uint32_t n0 = wave * 32u * kNI;
+    const uint32_t nb1 = up(a.h1, 32) / 32u, nb2 = up(a.h2, 32) / 32u;
+    const uint32_t cnt1 = nb1 > wave * kNI ? (nb1 - wave * kNI < (uint32_t)kNI ? nb1 - wave * kNI : (uint32_t)kNI) : 0u;
+    const uint32_t cnt2 = nb2 > wave * kNI ? (nb2 - wave * kNI < (uint32_t)kNI ? nb2 - wave * kNI : (uint32_t)kNI) : 0u;
+
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t row0 = tile * FBM;
+        __syncthreads(); // the previous tile's readers are done with H and s_flow
+        if (tid < FBM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : 0xFFFFFFFFu;
+        __syncthreads();
+        // input tile: gather, standardise, clamp, round to bfloat16; 8 values per thread per pass
+        const uint32_t chunks = k1p / 8u;
+        for (uint32_t g = tid; g < FBM * chunks; g += kWaves * 64u) {
+            const uint32_t r = g / chunks, k = (g - r * chunks) * 8u;
+            const uint32_t flow = s_flow[r];
+            float z[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) z[q] = 0.f;
+            if (flow != 0xFFFFFFFFu) {
+                const float* p = a.feat + (size_t)flow * a.feat_ld + k;
+                if (k + 8u <= a.n_in && (a.feat_ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0) {
+                    const float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
+                    z[0] = x0.x; z[1] = x0.y; z[2] = x0.z; z[3] = x0.w;
+                    z[4] = x1.x; z[5] = x1.y; z[6] = x1.z; z[7] = x1.w;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) z[q] = k + q < a.n_in ? p[q] : 0.f;
+                }
+                if (a.mu) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        if (k + q < a.n_in) {
+                            const float d = z[q] - a.mu[k + q];
+                            float t = d * a.inv_sigma[k + q];
+                            t = t < -a.clamp ? -a.clamp : t;
+                            z[q] = t > a.clamp ? a.clamp : t;
+                        }
+                    }
+                }
+            }
+            *reinterpret_cast<uint4*>(H + r * ldx + k) =
+                make_uint4(pack_bf16(z[0], z[1]), pack_bf16(z[2], z[3]), pack_bf16(z[4], z[5]), pack_bf16(z[6], z[7]));
+        }
+        __syncthreads();
+
+        f32x16 acc[kMI][kNI];
+        // layer 1
+        zero_acc(acc);
+        wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, cnt1, lane, acc);
+        __syncthreads(); // every wave has read the input tile; H may be overwritten
+        store_hidden(H, acc, a.b1, n0, a.h1, k2p, lane);
+        __syncthreads();
+        // layer 2
+        zero_acc(acc);
+        wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, cnt2, lane, acc);
+        __syncthreads();
+        store_hidden(H, acc, a.b2, n0, a.h2, k3p, lane);
+        __syncthreads();
+        // layer 3: wave w < 4 takes rows [32w, 32w+32) and all (padded) 32 classes; the accumulator
+        // is transposed as above: lane l holds 16 classes of row l%32, its partner l^32 the others
+        if (wave < 4u) {
+            f32x16 c3;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) c3[v] = 0.f;
+            const uint16_t* arow = H + (wave * 32u + (lane & 31u)) * LDH + 8u * (lane >> 5);
+            const uint32_t KS = k3p / 16u;
+            for (uint32_t ks = 0; ks < KS; ++ks) {
+                const bf16x8 fa = as_frag(*reinterpret_cast<const uint4*>(arow + ks * 16u));
+                const bf16x8 fb = as_frag(a.w3s[(size_t)ks * 64u + lane]);
+                c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, c3, 0, 0, 0);
+            }
+            const uint32_t r = wave * 32u + (lane & 31u);
+            const bool row_ok = row0 + r < total;
+            uint32_t best = 0xFFFFFFFFu;
+            float bv = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t c = 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3); // ascending in v
+                if (c < a.c) {
+                    const float y = c3[v] + a.b3[c];
+                    if (a.logits && row_ok) a.logits[(size_t)(row0 + r) * a.c + c] = y;
+                    if (best == 0xFFFFFFFFu || y > bv) {
+                        bv = y;
+                        best = c;
+                    }
+                }
+            }
+            // combine the two halves of the row: larger value wins, the lower class on a tie
+            const float ov = __shfl_xor(bv, 32, 64);
+            const uint32_t ob = (uint32_t)__shfl_xor((int)best, 32, 64);
+            if (ob != 0xFFFFFFFFu && (best == 0xFFFFFFFFu || ov > bv || (ov == bv && ob < best))) best = ob;
+            if (lane < 32u && row_ok) a.labels[s_flow[r]] = (uint16_t)best;
+        }
+    }
+}
+
+constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + FBM * 4;
+
+} // namespace
+
+namespace sf {
+
+bool slow_fused_ok(const sf_mlp* m, bool raw_input)
+{
+    return m->dtype == SF_BF16 && !raw_input && m->n_in <= HMAX && m->n_h1 <= HMAX && m->n_h2 <= HMAX && m->n_classes <= 32;
+}
+
+static size_t sw_bytes(uint32_t N, uint32_t K) { return align_up((size_t)(up(N, 32) / 32) * (up(K, 16) / 16) * 64 * 16); }
+
+size_t slow_fused_ws_bytes(const sf_mlp* m)
+{
+    return sw_bytes(m->n_h1, m->n_in) + sw_bytes(m->n_h2, m->n_h1) + sw_bytes(32, m->n_h2) + 3 * kAlign;
+}
+
+int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
+               const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* m, float* logits, uint16_t* labels)
+{
+    char* p = (char*)ws;
+    uint4* w1s = (uint4*)p;
+    p += sw_bytes(m->n_h1, m->n_in);
+    uint4* w2s = (uint4*)p;
+    p += sw_bytes(m->n_h2, m->n_h1);
+    uint4* w3s = (uint4*)p;
+    struct {
+        const void* w;
+        uint32_t N, K, NB;
+        uint4* out;
+    } jobs[3] = {{m->w1, m->n_h1, m->n_in, up(m->n_h1, 32) / 32, w1s},
+                 {m->w2, m->n_h2, m->n_h1, up(m->n_h2, 32) / 32, w2s},
+                 {m->w3, m->n_classes, m->n_h2, 1u, w3s}};
+    for (auto& j : jobs) {
+        const uint32_t KS = up(j.K, 16) / 16, total = j.NB * KS * 64;
+        uint32_t blocks = (total + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        reorder_weights<<<blocks, 256, 0, ctx->stream>>>((const uint16_t*)j.w, j.N, j.K, j.NB, KS, j.out);
+        SF_LAUNCH_CHECK(ctx, "reorder_weights");
+    }
+    FusedArgs a;
+    a.esc_idx = esc_idx;
+    a.esc_count = esc_count;
+    a.esc_cap = esc_cap;
+    a.feat = feat;
+    a.feat_ld = feat_ld;
+    a.mu = m->mu;
+    a.inv_sigma = m->inv_sigma;
+    a.clamp = m->clamp;
+    a.n_in = m->n_in;
+    a.h1 = m->n_h1;
+    a.h2 = m->n_h2;
+    a.c = m->n_classes;
+    a.w1s = w1s;
+    a.w2s = w2s;
+    a.w3s = w3s;
+    a.b1 = m->b1;
+    a.b2 = m->b2;
+    a.b3 = m->b3;
+    a.logits = logits;
+    a.labels = labels;
+    SF_HIP(ctx, hipFuncSetAttribute((const void*)mlp_fused, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds));
+    uint32_t tiles_cap = (esc_cap + FBM - 1) / FBM;
+    uint32_t grid = (uint32_t)ctx->n_cu; // one block per compute unit (its shared memory fills the unit)
+    if (grid > tiles_cap) grid = tiles_cap;
+    if (grid == 0) grid = 1;
+    mlp_fused<<<grid, kWaves * 64, kFusedLds, ctx->stream>>>(a);
+    SF_LAUNCH_CHECK(ctx, "mlp_fused");
+    return SF_OK;
+}
+
+} // namespace sf

@@ -13,6 +13,14 @@
 // binary32 models (small, used for the small workload) run on plain vector arithmetic.
 #include "common.h"
 
+namespace sf {
+// fused single-kernel form for narrow hidden layers (slow_fused.hip)
+bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
+size_t slow_fused_ws_bytes(const sf_mlp* mlp);
+int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
+               const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* mlp, float* logits, uint16_t* labels);
+} // namespace sf
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -455,6 +463,12 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
     }
 
     sf::Carve ws(ctx);
+    if (sf::slow_fused_ok(mlp, raw_src != nullptr)) {
+        const size_t need = sf::slow_fused_ws_bytes(mlp);
+        void* w = ws.take(need);
+        if (!w) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace too small for %zu bytes of re-ordered weights", need);
+        return sf::slow_fused(ctx, w, feat, feat_ld, esc_idx, esc_count, esc_cap, mlp, logits, labels);
+    }
     const bool bf = mlp->dtype == SF_BF16;
     const uint32_t ld1 = bf ? pad64(mlp->n_h1) : mlp->n_h1, ld2 = bf ? pad64(mlp->n_h2) : mlp->n_h2;
     const size_t row_bytes = bf ? ((size_t)ld1 + ld2) * 2 : ((size_t)mlp->n_in + ld1 + ld2 + mlp->n_classes) * 4;
