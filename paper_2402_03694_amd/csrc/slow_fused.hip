@@ -149,30 +149,29 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
     }
 }
 
-// H[row][col] = bfloat16(relu(acc + bias)) for the wave's columns; columns in [n_valid, n_pad) become zeros
-__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], const float* __restrict__ bias,
+// H[row][col] = bfloat16(relu(acc + bias)) for the wave's columns.  Columns in [n_valid, n_pad) come out as
+// zeros by themselves: their weights and their (shared-memory) bias entries are zero.
+__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], const float* sbias,
                                              uint32_t n0, uint32_t n_valid, uint32_t n_pad, uint32_t lane)
 {
+    (void)n_valid;
 #pragma unroll
     for (int j = 0; j < kNI; ++j) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5); // first of 4 consecutive columns
             if (col < n_pad) {
-                float b[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) b[q] = col + q < n_valid ? bias[col + q] : 0.f;
+                const float4 b = *reinterpret_cast<const float4*>(sbias + col);
 #pragma unroll
                 for (int i = 0; i < kMI; ++i) {
                     const uint32_t row = i * 32u + (lane & 31u);
-                    float y[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        y[q] = acc[i][j][4 * g + q] + b[q];
-                        y[q] = y[q] > 0.f ? y[q] : 0.f;
-                        y[q] = col + q < n_valid ? y[q] : 0.f;
-                    }
-                    *reinterpret_cast<uint2*>(H + row * LDH + col) = make_uint2(pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3]));
+                    float y0 = acc[i][j][4 * g + 0] + b.x, y1 = acc[i][j][4 * g + 1] + b.y;
+                    float y2 = acc[i][j][4 * g + 2] + b.z, y3 = acc[i][j][4 * g + 3] + b.w;
+                    y0 = y0 > 0.f ? y0 : 0.f;
+                    y1 = y1 > 0.f ? y1 : 0.f;
+                    y2 = y2 > 0.f ? y2 : 0.f;
+                    y3 = y3 > 0.f ? y3 : 0.f;
+                    *reinterpret_cast<uint2*>(H + row * LDH + col) = make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3));
                 }
             }
         }
@@ -194,6 +193,9 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t* H = reinterpret_cast<uint16_t*>(smem);                            // [128][LDH]; also the input tile
     uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)FBM * LDH * 2); // [128]
+    float* s_b1 = reinterpret_cast<float*>(s_flow + FBM);                          // [HMAX], zero past h1
+    float* s_b2 = s_b1 + HMAX;                                                     // [HMAX], zero past h2
+    float* s_b3 = s_b2 + HMAX;                                                     // [32], zero past c
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     uint32_t total = *a.esc_count;
     total = total < a.esc_cap ? total : a.esc_cap;
@@ -205,6 +207,11 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
     const uint32_t cnt1 = nb1 > wave * kNI ? (nb1 - wave * kNI < (uint32_t)kNI ? nb1 - wave * kNI : (uint32_t)kNI) : 0u;
     const uint32_t cnt2 = nb2 > wave * kNI ? (nb2 - wave * kNI < (uint32_t)kNI ? nb2 - wave * kNI : (uint32_t)kNI) : 0u;
 
+    for (uint32_t q = tid; q < (uint32_t)HMAX; q += kWaves * 64u) {
+        s_b1[q] = q < a.h1 ? a.b1[q] : 0.f;
+        s_b2[q] = q < a.h2 ? a.b2[q] : 0.f;
+        if (q < 32u) s_b3[q] = q < a.c ? a.b3[q] : 0.f;
+    }
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint32_t row0 = tile * FBM;
         __syncthreads(); // the previous tile's readers are done with H and s_flow
@@ -250,27 +257,40 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
         zero_acc(acc);
         wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, cnt1, lane, acc);
         __syncthreads(); // every wave has read the input tile; H may be overwritten
-        store_hidden(H, acc, a.b1, n0, a.h1, k2p, lane);
+        store_hidden(H, acc, s_b1, n0, a.h1, k2p, lane);
         __syncthreads();
         // layer 2
         zero_acc(acc);
         wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, cnt2, lane, acc);
         __syncthreads();
-        store_hidden(H, acc, a.b2, n0, a.h2, k3p, lane);
+        store_hidden(H, acc, s_b2, n0, a.h2, k3p, lane);
         __syncthreads();
         // layer 3: wave w < 4 takes rows [32w, 32w+32) and all (padded) 32 classes; the accumulator
         // is transposed as above: lane l holds 16 classes of row l%32, its partner l^32 the others
         if (wave < 4u) {
-            f32x16 c3;
+            f32x16 c3, c3b;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) c3[v] = 0.f;
+            for (int v = 0; v < 16; ++v) c3[v] = c3b[v] = 0.f;
             const uint16_t* arow = H + (wave * 32u + (lane & 31u)) * LDH + 8u * (lane >> 5);
             const uint32_t KS = k3p / 16u;
-            for (uint32_t ks = 0; ks < KS; ++ks) {
-                const bf16x8 fa = as_frag(*reinterpret_cast<const uint4*>(arow + ks * 16u));
-                const bf16x8 fb = as_frag(a.w3s[(size_t)ks * 64u + lane]);
-                c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, c3, 0, 0, 0);
+            // the hidden accumulators are dead here, so a whole layer of weight operands fits in
+            // registers: one memory latency instead of one per k-step
+            for (uint32_t kb = 0; kb < KS; kb += 16u) {
+                uint4 wv[16];
+#pragma unroll
+                for (int s = 0; s < 16; ++s) wv[s] = a.w3s[(size_t)(kb + s < KS ? kb + s : KS - 1u) * 64u + lane];
+#pragma unroll
+                for (int s = 0; s < 16; s += 2) {
+                    if (kb + s < KS)
+                        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            as_frag(wv[s]), as_frag(*reinterpret_cast<const uint4*>(arow + (kb + s) * 16u)), c3, 0, 0, 0);
+                    if (kb + s + 1 < KS)
+                        c3b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            as_frag(wv[s + 1]), as_frag(*reinterpret_cast<const uint4*>(arow + (kb + s + 1) * 16u)), c3b, 0, 0, 0);
+                }
             }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) c3[v] += c3b[v];
             const uint32_t r = wave * 32u + (lane & 31u);
             const bool row_ok = row0 + r < total;
             uint32_t best = 0xFFFFFFFFu;
@@ -279,7 +299,7 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
             for (int v = 0; v < 16; ++v) {
                 const uint32_t c = 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3); // ascending in v
                 if (c < a.c) {
-                    const float y = c3[v] + a.b3[c];
+                    const float y = c3[v] + s_b3[c];
                     if (a.logits && row_ok) a.logits[(size_t)(row0 + r) * a.c + c] = y;
                     if (best == 0xFFFFFFFFu || y > bv) {
                         bv = y;
@@ -296,7 +316,7 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
     }
 }
 
-constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + FBM * 4;
+constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + FBM * 4 + (2 * HMAX + 32) * 4;
 
 } // namespace
 
