@@ -77,34 +77,45 @@ struct FastArgs {
 #endif
 constexpr int kIlp = SF_FAST_ILP; // trees walked at once per lane
 
-template <int BS, bool WANT_LEAF>
+// BS lanes per block; S lanes share one flow, lane group g of S walks trees g, g+S, g+2S, ...
+// Splitting a flow over S lanes divides the shared memory per lane by S (the feature tile is per
+// flow), which is what limits the number of resident waves.
+template <int BS, int S, bool WANT_LEAF>
 __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
 {
-    constexpr uint32_t kColShift = BS == 256 ? 10 : (BS == 128 ? 9 : 8); // log2(bytes per feature column)
+    constexpr uint32_t FPB = BS / S;       // flows per block
+    constexpr uint32_t FPW = 64 / S;       // flows per wave
+    constexpr uint32_t kColShift = FPB == 256 ? 10 : (FPB == 128 ? 9 : (FPB == 64 ? 8 : 7)); // log2(bytes per feature column)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     const uint32_t F = a.n_features, C = a.n_classes, T = a.n_trees;
     const uint32_t top_recs = recs_upto(a.top_pairs);      // records per tree held in shared memory
-    float* xT = reinterpret_cast<float*>(smem_raw);                          // [F][BS]
-    // vote counters, 32 / vote_bits classes per word: [ceil(C * vote_bits / 32)][BS]
+    float* xT = reinterpret_cast<float*>(smem_raw);                          // [F][FPB]
+    // vote counters, 32 / vote_bits classes per word, one column per LANE: [vote_words][BS]
     const uint32_t per_shift = a.vote_bits == 8 ? 2u : 1u; // log2(counters per word)
     const uint32_t vote_words = (C + (1u << per_shift) - 1u) >> per_shift;
-    uint32_t* vT = reinterpret_cast<uint32_t*>(xT + (size_t)F * BS);
+    uint32_t* vT = reinterpret_cast<uint32_t*>(xT + (size_t)F * FPB);
     uint4* topT = reinterpret_cast<uint4*>(vT + (size_t)vote_words * BS);    // [T][top_recs]
-    const uint32_t tid = threadIdx.x;
-    const uint32_t i = blockIdx.x * BS + tid;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t grp = lane / FPW;                       // which share of the trees this lane walks
+    const uint32_t slot = wave * FPW + (lane % FPW);       // flow slot in the block's tile
+    const uint32_t i = blockIdx.x * FPB + slot;
     const bool live = i < a.n_flows;
     const uint32_t row = live ? i : a.n_flows - 1; // idle lanes walk a valid row, write nothing
-    const float* x = a.feat + (size_t)row * a.ld;
-    if ((a.ld & 3u) == 0 && (F & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0) {
-        for (uint32_t q = 0; q < F / 4; ++q) {
-            const float4 v = reinterpret_cast<const float4*>(x)[q];
-            xT[(4 * q + 0) * BS + tid] = v.x;
-            xT[(4 * q + 1) * BS + tid] = v.y;
-            xT[(4 * q + 2) * BS + tid] = v.z;
-            xT[(4 * q + 3) * BS + tid] = v.w;
+    {
+        // the S lanes of a flow each copy 1/S of its row into the flow's column
+        const float* x = a.feat + (size_t)row * a.ld;
+        if ((a.ld & 3u) == 0 && (F % (4u * S)) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0) {
+            const uint32_t per = F / 4u / S;
+            for (uint32_t q = grp * per; q < (grp + 1u) * per; ++q) {
+                const float4 v = reinterpret_cast<const float4*>(x)[q];
+                xT[(4 * q + 0) * FPB + slot] = v.x;
+                xT[(4 * q + 1) * FPB + slot] = v.y;
+                xT[(4 * q + 2) * FPB + slot] = v.z;
+                xT[(4 * q + 3) * FPB + slot] = v.w;
+            }
+        } else {
+            for (uint32_t f = grp; f < F; f += S) xT[f * FPB + slot] = x[f];
         }
-    } else {
-        for (uint32_t f = 0; f < F; ++f) xT[f * BS + tid] = x[f];
     }
     for (uint32_t c = 0; c < vote_words; ++c) vT[c * BS + tid] = 0;
     const uint32_t n_rec = recs_upto(pair_levels(a.depth));
@@ -113,13 +124,13 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
         const uint32_t t = q / top_recs, r = q - t * top_recs;
         topT[q] = recs[(size_t)t * n_rec + r];
     }
-    __syncthreads(); // the staged records are shared by the block
+    __syncthreads(); // the staged records and the feature columns are shared
 
     const uint32_t depth = a.depth;
     const uint32_t full_pairs = depth >> 1;
     const uint32_t lds_pairs = a.top_pairs < full_pairs ? a.top_pairs : full_pairs;
     const bool odd = depth & 1u;
-    const char* xlane = reinterpret_cast<const char*>(xT) + tid * 4u; // the lane's column
+    const char* xlane = reinterpret_cast<const char*>(xT) + slot * 4u; // the flow's column
     uint32_t* vcol = vT + tid;
     const uint32_t rec_bytes = n_rec * 16u, top_bytes = top_recs * 16u;
     const uint32_t leaf_base = recs_upto(full_pairs); // record index of position 0 on tree level 2*full_pairs
@@ -139,12 +150,18 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
         (O) = 4u * (O) + (r0 ? inc_r : inc_l);                                                            \
     } while (0)
 
-    for (uint32_t t0 = 0; t0 < T; t0 += kIlp) {
+    // lane group g walks trees g, g+S, ...; every group runs the same number of rounds so that
+    // the loop stays wave-uniform; a slot past the last tree repeats it and does not vote
+    const uint32_t per_grp = (T + S - 1u) / S;
+    for (uint32_t q0 = 0; q0 < per_grp; q0 += kIlp) {
         uint32_t o[kIlp], tt[kIlp];
+        bool tv[kIlp];
 #pragma unroll
         for (int u = 0; u < kIlp; ++u) {
+            const uint32_t t = (q0 + u) * S + grp;
             o[u] = 0;
-            tt[u] = t0 + u < T ? t0 + u : T - 1; // the tail repeats the last tree and does not vote
+            tv[u] = q0 + u < per_grp && t < T;
+            tt[u] = tv[u] ? t : T - 1u;
         }
         uint32_t j = 0;
         for (; j < lds_pairs; ++j) {
@@ -186,42 +203,52 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
         for (int u = 0; u < kIlp; ++u) lab[u] = a.leaf_label[(size_t)tt[u] * n_leaf + leaf[u]];
 #pragma unroll
         for (int u = 0; u < kIlp; ++u) {
-            if (t0 + u < T) {
+            if (tv[u]) {
                 const uint32_t l = lab[u] < C ? lab[u] : C - 1u; // clamp: a bad label must not leave the tile
                 // only this lane touches its column; the add is one shared-memory instruction
                 atomicAdd(&vcol[(l >> per_shift) * BS], 1u << ((l & ((1u << per_shift) - 1u)) * a.vote_bits));
-                if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + t0 + u] = (uint16_t)leaf[u];
+                if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + tt[u]] = (uint16_t)leaf[u];
             }
         }
     }
 #undef SF_PAIR_STEP
-    if (!live) return;
+    if (S > 1) __syncthreads(); // the S partial vote columns of a flow are summed by its first lane
+    if (!live || grp != 0) return;
     uint32_t best = 0, bestv = 0;
     const uint32_t vmask = (1u << a.vote_bits) - 1u;
-    for (uint32_t c = 0; c < C; ++c) {
-        const uint32_t v = (vcol[(c >> per_shift) * BS] >> ((c & ((1u << per_shift) - 1u)) * a.vote_bits)) & vmask;
-        if (a.votes) a.votes[(size_t)i * C + c] = (uint16_t)v;
-        if (c == 0 || v > bestv) {
-            bestv = v;
-            best = c;
+    for (uint32_t w = 0; w < vote_words; ++w) {
+        uint32_t word = 0; // packed fields cannot overflow: the sum over groups is at most n_trees
+#pragma unroll
+        for (int g = 0; g < S; ++g) word += vT[w * BS + tid + g * FPW];
+        for (uint32_t k = 0; k < (1u << per_shift); ++k) {
+            const uint32_t c = (w << per_shift) + k;
+            if (c < C) {
+                const uint32_t v = (word >> (k * a.vote_bits)) & vmask;
+                if (a.votes) a.votes[(size_t)i * C + c] = (uint16_t)v;
+                if (c == 0 || v > bestv) {
+                    bestv = v;
+                    best = c;
+                }
+            }
         }
     }
     a.pred[i] = (uint16_t)best;
     a.top[i] = (uint16_t)bestv;
 }
 
-template <int BS>
+template <int BS, int S>
 int launch_votes(sf_ctx* ctx, const FastArgs& a, size_t lds)
 {
-    const uint32_t grid = (a.n_flows + BS - 1) / BS;
+    const uint32_t fpb = BS / S;
+    const uint32_t grid = (a.n_flows + fpb - 1) / fpb;
     if (a.leaf_idx) {
-        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, true>,
+        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, true>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        forest_votes<BS, true><<<grid, BS, lds, ctx->stream>>>(a);
+        forest_votes<BS, S, true><<<grid, BS, lds, ctx->stream>>>(a);
     } else {
-        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, false>,
+        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, false>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        forest_votes<BS, false><<<grid, BS, lds, ctx->stream>>>(a);
+        forest_votes<BS, S, false><<<grid, BS, lds, ctx->stream>>>(a);
     }
     SF_LAUNCH_CHECK(ctx, "forest_votes");
     return SF_OK;
@@ -287,14 +314,22 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     a.pred = pred;
     a.top = top_votes;
     a.leaf_idx = leaf_idx;
-    // Shared memory per block: a feature column and packed vote counters per lane, plus the staged
-    // top records of every tree.  Two blocks per compute unit (160 KB) keep eight waves resident;
-    // what is left of a block's half goes to the top records.
+    // Shared memory per block of 256 lanes: a feature column per FLOW, packed vote counters per
+    // lane, and the staged top records of every tree.  With two lanes per flow three blocks (12
+    // waves) stay resident instead of two, which pays while the deep records of the trees in
+    // flight still fit the first-level cache (measured: faster up to depth 10, slower at 12,
+    // where more waves mean more distinct trees in flight and more cache misses).
     a.vote_bits = a.n_trees <= 255 ? 8u : 16u;
     const uint32_t vote_words = (a.n_classes * a.vote_bits + 31u) / 32u;
-    const size_t per_lane = ((size_t)a.n_features + vote_words) * 4;
-    const size_t budget = 80 * 1024 - 512;
-    const uint32_t bs = per_lane * 256 <= budget ? 256u : (per_lane * 128 <= budget ? 128u : 64u);
+#ifdef SF_FAST_SPLIT
+    const uint32_t split = SF_FAST_SPLIT;
+#else
+    const uint32_t split = (a.n_trees >= 32 && recs_upto(pair_levels(forest->depth)) * 16u <= 8192u) ? 2u : 1u;
+#endif
+    const size_t fixed = (size_t)a.n_features * 4 * (256 / split) + (size_t)vote_words * 4 * 256;
+    size_t budget = 160 * 1024 / 3 - 256;
+    if (fixed + (size_t)a.n_trees * 16 > budget) budget = 80 * 1024 - 512;
+    if (fixed + (size_t)a.n_trees * 16 > budget) budget = 160 * 1024 - 1024;
     const uint32_t full_pairs = forest->depth / 2;
     uint32_t top_pairs = 0;
 #ifdef SF_FAST_TOP_PAIRS
@@ -303,11 +338,11 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     const uint32_t want_pairs = 8;
 #endif
     while (top_pairs < full_pairs && top_pairs < want_pairs &&
-           per_lane * bs + (size_t)a.n_trees * recs_upto(top_pairs + 1) * 16 <= budget)
+           fixed + (size_t)a.n_trees * recs_upto(top_pairs + 1) * 16 <= budget)
         ++top_pairs;
     a.top_pairs = top_pairs;
-    const size_t lds = per_lane * bs + (size_t)a.n_trees * recs_upto(top_pairs) * 16;
-    if (bs == 256) return launch_votes<256>(ctx, a, lds);
-    if (bs == 128) return launch_votes<128>(ctx, a, lds);
-    return launch_votes<64>(ctx, a, lds);
+    const size_t lds = fixed + (size_t)a.n_trees * recs_upto(top_pairs) * 16;
+    if (lds > 160 * 1024) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_fast_infer: %zu bytes of shared memory needed", lds);
+    if (split == 2) return launch_votes<256, 2>(ctx, a, lds);
+    return launch_votes<256, 1>(ctx, a, lds);
 }
