@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--target", type=float, default=-1.0, help="override the escalated-fraction target")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (flows would be sharded "
@@ -151,6 +153,12 @@ def main():
         if ev:
             ev[4].record()
 
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)              # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -214,7 +222,7 @@ def main():
         "p50_ms": float(np.median(call_ms.sum(axis=1))), "p99_ms": float(np.percentile(call_ms.sum(axis=1), 99)),
     }
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample or min(n, 1 << 18)
+        sample = args.cpu_sample or min(n, 1 << 20)
         out["cpu_baseline"] = cpu_baseline(cfg, sample, vmin)
     print(json.dumps(out))
 
