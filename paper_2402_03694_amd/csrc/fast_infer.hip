@@ -327,7 +327,11 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     const uint32_t split = (a.n_trees >= 32 && recs_upto(pair_levels(forest->depth)) * 16u <= 8192u) ? 2u : 1u;
 #endif
     const size_t fixed = (size_t)a.n_features * 4 * (256 / split) + (size_t)vote_words * 4 * 256;
+#ifdef SF_FAST_BUDGET
+    size_t budget = SF_FAST_BUDGET;
+#else
     size_t budget = 160 * 1024 / 3 - 256;
+#endif
     if (fixed + (size_t)a.n_trees * 16 > budget) budget = 80 * 1024 - 512;
     if (fixed + (size_t)a.n_trees * 16 > budget) budget = 160 * 1024 - 1024;
     const uint32_t full_pairs = forest->depth / 2;

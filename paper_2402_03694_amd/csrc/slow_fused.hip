@@ -30,6 +30,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int FBM = 128;      // rows per tile
 constexpr int HMAX = 512;     // widest hidden layer
 constexpr int LDH = HMAX + 8; // activation row stride in elements
+constexpr uint32_t kPadK = 64; // every K is padded to this (four k-steps of 16)
 
 __host__ __device__ inline uint32_t up(uint32_t x, uint32_t m) { return (x + m - 1u) / m * m; }
 
@@ -104,47 +105,53 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 constexpr int kWaves = 8;  // waves per block
 constexpr int kNI = 2;     // 32-column blocks per wave (64 columns)
 constexpr int kMI = 4;     // 32-row blocks per wave (all 128 rows)
-constexpr int kAhead = 2;  // k-steps of weight operands in flight
+constexpr int kRing = 4;   // weight operands of this many k-steps are in flight (K is padded to 16 * kRing)
 
 // The MFMA is issued with the WEIGHT operand first, so the 32x32 accumulator block holds the
 // output transposed: element v of lane l is output column 8*(v/4) + 4*(l/32) + v%4 of
 // activation row l%32.  Four consecutive v are four consecutive columns of one row, which lets
 // the epilogue write 8 bytes at a time.
-// acc[i][j] += W[cols of block nb0+j][K] * A[rows 32i..32i+32)[K]^T
+// acc[i][j] += W[cols of block nb0+j][K] * A[rows 32i..32i+32)[K]^T, KS a multiple of kRing.
+// The weight operands sit in a ring of kRing register buffers; a buffer is refilled for k-step
+// ks + kRing right after the MFMAs of k-step ks have been issued, so no load is waited for in the
+// step that issues it and no register is copied.  wbase is wave-uniform; lane_off = 16 * lane.
 __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const uint4* __restrict__ ws, uint32_t KS,
-                                          uint32_t nb0, uint32_t nb_cnt, uint32_t lane, f32x16 (&acc)[kMI][kNI])
+                                          uint32_t nb0, uint32_t nb_total, uint32_t lane, f32x16 (&acc)[kMI][kNI])
 {
-    if (nb_cnt == 0) return;
+    if (nb0 >= nb_total) return; // this wave has no columns in this layer
     const uint16_t* arow = A + (lane & 31u) * lda + 8u * (lane >> 5);
-    const uint4* wl = ws + (size_t)nb0 * KS * 64u + lane;
-    uint4 fb[kAhead][kNI];
+    // a column block past the end repeats the last one; its results are never stored
+    const uint4* wl[kNI];
 #pragma unroll
-    for (int s = 0; s < kAhead; ++s)
+    for (int j = 0; j < kNI; ++j) {
+        const uint32_t nb = nb0 + j < nb_total ? nb0 + j : nb_total - 1u;
+        wl[j] = ws + (size_t)nb * KS * 64u;
+    }
+    uint4 fb[kRing][kNI];
 #pragma unroll
-        for (int j = 0; j < kNI; ++j) {
-            const uint32_t kk = (uint32_t)s < KS ? (uint32_t)s : KS - 1u;
-            fb[s][j] = (uint32_t)j < nb_cnt ? wl[((size_t)j * KS + kk) * 64u] : make_uint4(0, 0, 0, 0);
-        }
-    for (uint32_t ks = 0; ks < KS; ++ks) {
-        uint4 nx[kNI];
-        const uint32_t kn = ks + kAhead < KS ? ks + kAhead : KS - 1u;
+    for (int s = 0; s < kRing; ++s)
 #pragma unroll
-        for (int j = 0; j < kNI; ++j)
-            nx[j] = (uint32_t)j < nb_cnt ? wl[((size_t)j * KS + kn) * 64u] : make_uint4(0, 0, 0, 0);
-        bf16x8 fa[kMI];
+        for (int j = 0; j < kNI; ++j) fb[s][j] = wl[j][s * 64 + lane];
+    for (uint32_t k0 = 0; k0 < KS; k0 += kRing) {
 #pragma unroll
-        for (int i = 0; i < kMI; ++i) fa[i] = as_frag(*reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda + ks * 16u));
+        for (int s = 0; s < kRing; ++s) {
+            bf16x8 fa[kMI];
 #pragma unroll
-        for (int j = 0; j < kNI; ++j) {
-            const bf16x8 b = as_frag(fb[0][j]);
+            for (int i = 0; i < kMI; ++i)
+                fa[i] = as_frag(*reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda + (k0 + s) * 16u));
 #pragma unroll
-            for (int i = 0; i < kMI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[i], acc[i][j], 0, 0, 0);
-        }
+            for (int j = 0; j < kNI; ++j) {
+                const bf16x8 b = as_frag(fb[s][j]);
 #pragma unroll
-        for (int j = 0; j < kNI; ++j) {
+                for (int i = 0; i < kMI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[i], acc[i][j], 0, 0, 0);
+            }
+            // refill for k-step k0 + s + kRing; past the end this reads the next block (or the
+            // padding behind the last one) and is never used
 #pragma unroll
-            for (int s = 0; s + 1 < kAhead; ++s) fb[s][j] = fb[s + 1][j];
-            fb[kAhead - 1][j] = nx[j];
+            for (int j = 0; j < kNI; ++j) fb[s][j] = wl[j][(k0 + kRing + s) * 64u + lane];
+            // keep the refill here: left alone, the scheduler sinks it to just before its use
+            // (to save registers) and every k-step then waits a full memory latency
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -188,135 +195,217 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[kMI][kNI])
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 }
 
+constexpr uint32_t kNoFlow = 0xFFFFFFFFu;
+constexpr int kXr = 2; // 8-value input chunks a thread can hold in registers for the next tile
+
+// raw feature values [k, k+8) of one flow (zeros for a missing flow or past n_in)
+__device__ __forceinline__ void load_chunk(const FusedArgs& a, uint32_t flow, uint32_t k, float (&z)[8])
+{
+#pragma unroll
+    for (int q = 0; q < 8; ++q) z[q] = 0.f;
+    if (flow == kNoFlow) return;
+    const float* p = a.feat + (size_t)flow * a.feat_ld + k;
+    if (k + 8u <= a.n_in && (a.feat_ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0) {
+        const float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
+        z[0] = x0.x; z[1] = x0.y; z[2] = x0.z; z[3] = x0.w;
+        z[4] = x1.x; z[5] = x1.y; z[6] = x1.z; z[7] = x1.w;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) z[q] = k + q < a.n_in ? p[q] : 0.f;
+    }
+}
+
+// standardise, clamp, round to bfloat16 and store one chunk of the input tile
+__device__ __forceinline__ void store_chunk(const FusedArgs& a, uint16_t* dst, uint32_t k, float (&z)[8])
+{
+    if (a.mu) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (k + q < a.n_in) {
+                const float d = z[q] - a.mu[k + q];
+                float t = d * a.inv_sigma[k + q];
+                t = t < -a.clamp ? -a.clamp : t;
+                z[q] = t > a.clamp ? a.clamp : t;
+            }
+        }
+    }
+    *reinterpret_cast<uint4*>(dst) =
+        make_uint4(pack_bf16(z[0], z[1]), pack_bf16(z[2], z[3]), pack_bf16(z[4], z[5]), pack_bf16(z[6], z[7]));
+}
+
+// Tile schedule (one block, eight waves, persistent over tiles t, t + gridDim.x, ...):
+//   top        the input tile is written from registers that were loaded during the previous
+//              tile's last layer; the flow ids of the NEXT tile are requested
+//   layer 1    MFMA, then the next tile's flow ids are parked in shared memory, epilogue -> H
+//   layer 2    MFMA, epilogue -> H; the last layer's weight operands are requested
+//   layer 3    the next tile's feature rows are requested (they arrive while layer 3 runs);
+//              8 waves = 4 row blocks x 2 halves of K; halves are summed through shared memory
 __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* H = reinterpret_cast<uint16_t*>(smem);                            // [128][LDH]; also the input tile
-    uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)FBM * LDH * 2); // [128]
-    float* s_b1 = reinterpret_cast<float*>(s_flow + FBM);                          // [HMAX], zero past h1
+    uint16_t* H = reinterpret_cast<uint16_t*>(smem);                              // [128][LDH]; also the input tile
+    uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)FBM * LDH * 2); // [2][128]: this tile, next tile
+    float* s_b1 = reinterpret_cast<float*>(s_flow + 2 * FBM);                      // [HMAX], zero past h1
     float* s_b2 = s_b1 + HMAX;                                                     // [HMAX], zero past h2
     float* s_b3 = s_b2 + HMAX;                                                     // [32], zero past c
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    float* s_part = s_b3 + 32;                                                     // [4][16][64] last-layer partial sums
+    // the wave index is the same in every lane: say so, and everything derived from it (column
+    // block, weight pointers) lives in scalar registers
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t total = *a.esc_count;
     total = total < a.esc_cap ? total : a.esc_cap;
     const uint32_t n_tiles = (total + FBM - 1) / FBM;
-    const uint32_t k1p = up(a.n_in, 16), k2p = up(a.h1, 16), k3p = up(a.h2, 16);
+    if (blockIdx.x >= n_tiles) return;
+    const uint32_t k1p = up(a.n_in, kPadK), k2p = up(a.h1, kPadK), k3p = up(a.h2, kPadK);
     const uint32_t ldx = k1p + 8; // input tile row stride
     const uint32_t n0 = wave * 32u * kNI;
     const uint32_t nb1 = up(a.h1, 32) / 32u, nb2 = up(a.h2, 32) / 32u;
-    const uint32_t cnt1 = nb1 > wave * kNI ? (nb1 - wave * kNI < (uint32_t)kNI ? nb1 - wave * kNI : (uint32_t)kNI) : 0u;
-    const uint32_t cnt2 = nb2 > wave * kNI ? (nb2 - wave * kNI < (uint32_t)kNI ? nb2 - wave * kNI : (uint32_t)kNI) : 0u;
+    const uint32_t chunks = k1p / 8u;
+    const bool in_regs = FBM * chunks <= (uint32_t)kXr * kWaves * 64u; // the whole input tile fits the threads' registers
 
-    for (uint32_t q = tid; q < (uint32_t)HMAX; q += kWaves * 64u) {
+    for (uint32_t q = threadIdx.x; q < (uint32_t)HMAX; q += kWaves * 64u) {
         s_b1[q] = q < a.h1 ? a.b1[q] : 0.f;
         s_b2[q] = q < a.h2 ? a.b2[q] : 0.f;
         if (q < 32u) s_b3[q] = q < a.c ? a.b3[q] : 0.f;
     }
+    float xr[kXr][8];
+    {
+        // first tile: flow ids and feature rows are fetched here, with nothing to overlap them
+        const uint32_t tid = threadIdx.x, row0 = blockIdx.x * FBM;
+        if (tid < FBM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : kNoFlow;
+        __syncthreads();
+        if (in_regs) {
+#pragma unroll
+            for (int u = 0; u < kXr; ++u) {
+                const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
+                load_chunk(a, r < (uint32_t)FBM ? s_flow[r] : kNoFlow, k, xr[u]);
+            }
+        }
+    }
+    uint32_t cur = 0;
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint32_t row0 = tile * FBM;
-        __syncthreads(); // the previous tile's readers are done with H and s_flow
-        if (tid < FBM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : 0xFFFFFFFFu;
-        __syncthreads();
-        // input tile: gather, standardise, clamp, round to bfloat16; 8 values per thread per pass
-        const uint32_t chunks = k1p / 8u;
-        for (uint32_t g = tid; g < FBM * chunks; g += kWaves * 64u) {
-            const uint32_t r = g / chunks, k = (g - r * chunks) * 8u;
-            const uint32_t flow = s_flow[r];
-            float z[8];
+        const uint32_t next_row0 = row0 + gridDim.x * FBM;
+        const bool has_next = tile + gridDim.x < n_tiles;
+        // Re-read the lane index behind an opaque barrier in every tile: otherwise every per-lane
+        // address of the tile body is hoisted out of this loop and spilled around the MFMA loops.
+        uint32_t tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const uint32_t lane = tid & 63u;
+        const uint32_t* flow_cur = s_flow + cur * FBM;
+        uint32_t* flow_next = s_flow + (cur ^ 1u) * FBM;
+        // flow ids of the next tile: requested now, parked in shared memory after layer 1
+        uint32_t nf = kNoFlow;
+        if (has_next && tid < FBM && next_row0 + tid < total) nf = a.esc_idx[next_row0 + tid];
+        // input tile of this tile (H is free: the previous tile's last layer ended with a barrier)
+        if (in_regs) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) z[q] = 0.f;
-            if (flow != 0xFFFFFFFFu) {
-                const float* p = a.feat + (size_t)flow * a.feat_ld + k;
-                if (k + 8u <= a.n_in && (a.feat_ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0) {
-                    const float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
-                    z[0] = x0.x; z[1] = x0.y; z[2] = x0.z; z[3] = x0.w;
-                    z[4] = x1.x; z[5] = x1.y; z[6] = x1.z; z[7] = x1.w;
-                } else {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) z[q] = k + q < a.n_in ? p[q] : 0.f;
-                }
-                if (a.mu) {
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        if (k + q < a.n_in) {
-                            const float d = z[q] - a.mu[k + q];
-                            float t = d * a.inv_sigma[k + q];
-                            t = t < -a.clamp ? -a.clamp : t;
-                            z[q] = t > a.clamp ? a.clamp : t;
-                        }
-                    }
-                }
+            for (int u = 0; u < kXr; ++u) {
+                const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
+                if (r < (uint32_t)FBM) store_chunk(a, H + r * ldx + k, k, xr[u]);
             }
-            *reinterpret_cast<uint4*>(H + r * ldx + k) =
-                make_uint4(pack_bf16(z[0], z[1]), pack_bf16(z[2], z[3]), pack_bf16(z[4], z[5]), pack_bf16(z[6], z[7]));
+        } else {
+            for (uint32_t g = tid; g < FBM * chunks; g += kWaves * 64u) {
+                const uint32_t r = g / chunks, k = (g - r * chunks) * 8u;
+                float z[8];
+                load_chunk(a, flow_cur[r], k, z);
+                store_chunk(a, H + r * ldx + k, k, z);
+            }
         }
         __syncthreads();
 
         f32x16 acc[kMI][kNI];
         // layer 1
         zero_acc(acc);
-        wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, cnt1, lane, acc);
+        wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc);
         __syncthreads(); // every wave has read the input tile; H may be overwritten
+        if (tid < FBM) flow_next[tid] = nf;
         store_hidden(H, acc, s_b1, n0, a.h1, k2p, lane);
         __syncthreads();
         // layer 2
         zero_acc(acc);
-        wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, cnt2, lane, acc);
+        wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc);
         __syncthreads();
         store_hidden(H, acc, s_b2, n0, a.h2, k3p, lane);
+        // layer 3: wave = (row block rb, half kh of K).  The hidden accumulators are dead, so a
+        // whole half-layer of weight operands fits in registers; they are requested before the
+        // barrier so that their latency overlaps it.
+        const uint32_t rb = wave & 3u, kh = wave >> 2;
+        const uint32_t KS3 = k3p / 16u, khalf = KS3 / 2u, kbeg = kh * khalf; // KS3 is a multiple of 4
+        uint4 wv[16];
+#pragma unroll
+        for (int s3 = 0; s3 < 16; ++s3)
+            wv[s3] = a.w3s[(size_t)(kbeg + ((uint32_t)s3 < khalf ? (uint32_t)s3 : khalf - 1u)) * 64u + lane];
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        // layer 3: wave w < 4 takes rows [32w, 32w+32) and all (padded) 32 classes; the accumulator
-        // is transposed as above: lane l holds 16 classes of row l%32, its partner l^32 the others
-        if (wave < 4u) {
+        // the next tile's feature rows: requested now, consumed at the top of the next iteration
+        if (has_next && in_regs) {
+#pragma unroll
+            for (int u = 0; u < kXr; ++u) {
+                const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
+                load_chunk(a, r < (uint32_t)FBM ? flow_next[r] : kNoFlow, k, xr[u]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        {
             f32x16 c3, c3b;
 #pragma unroll
             for (int v = 0; v < 16; ++v) c3[v] = c3b[v] = 0.f;
-            const uint16_t* arow = H + (wave * 32u + (lane & 31u)) * LDH + 8u * (lane >> 5);
-            const uint32_t KS = k3p / 16u;
-            // the hidden accumulators are dead here, so a whole layer of weight operands fits in
-            // registers: one memory latency instead of one per k-step
-            for (uint32_t kb = 0; kb < KS; kb += 16u) {
-                uint4 wv[16];
+            const uint16_t* arow = H + (rb * 32u + (lane & 31u)) * LDH + 8u * (lane >> 5);
+            for (uint32_t kb = 0; kb < khalf; kb += 16u) {
+                if (kb) {
 #pragma unroll
-                for (int s = 0; s < 16; ++s) wv[s] = a.w3s[(size_t)(kb + s < KS ? kb + s : KS - 1u) * 64u + lane];
+                    for (int s3 = 0; s3 < 16; ++s3)
+                        wv[s3] = a.w3s[(size_t)(kbeg + (kb + s3 < khalf ? kb + s3 : khalf - 1u)) * 64u + lane];
+                }
 #pragma unroll
-                for (int s = 0; s < 16; s += 2) {
-                    if (kb + s < KS)
+                for (int s3 = 0; s3 < 16; s3 += 2) {
+                    if (kb + s3 < khalf)
                         c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            as_frag(wv[s]), as_frag(*reinterpret_cast<const uint4*>(arow + (kb + s) * 16u)), c3, 0, 0, 0);
-                    if (kb + s + 1 < KS)
+                            as_frag(wv[s3]), as_frag(*reinterpret_cast<const uint4*>(arow + (kbeg + kb + s3) * 16u)), c3, 0, 0, 0);
+                    if (kb + s3 + 1 < khalf)
                         c3b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            as_frag(wv[s + 1]), as_frag(*reinterpret_cast<const uint4*>(arow + (kb + s + 1) * 16u)), c3b, 0, 0, 0);
+                            as_frag(wv[s3 + 1]), as_frag(*reinterpret_cast<const uint4*>(arow + (kbeg + kb + s3 + 1) * 16u)), c3b, 0, 0, 0);
                 }
             }
 #pragma unroll
             for (int v = 0; v < 16; ++v) c3[v] += c3b[v];
-            const uint32_t r = wave * 32u + (lane & 31u);
-            const bool row_ok = row0 + r < total;
-            uint32_t best = 0xFFFFFFFFu;
-            float bv = 0.f;
+            float* part = s_part + rb * (16 * 64);
+            if (kh == 1u) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const uint32_t c = 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3); // ascending in v
-                if (c < a.c) {
-                    const float y = c3[v] + s_b3[c];
-                    if (a.logits && row_ok) a.logits[(size_t)(row0 + r) * a.c + c] = y;
-                    if (best == 0xFFFFFFFFu || y > bv) {
-                        bv = y;
-                        best = c;
+                for (int v = 0; v < 16; ++v) part[v * 64 + lane] = c3[v];
+            }
+            __syncthreads(); // also: every wave is done reading H
+            if (kh == 0u) {
+                // the accumulator is transposed: lane l holds 16 classes of row l%32, lane l^32 the others
+                const uint32_t r = rb * 32u + (lane & 31u);
+                const bool row_ok = row0 + r < total;
+                uint32_t best = kNoFlow;
+                float bv = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t c = 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3); // ascending in v
+                    if (c < a.c) {
+                        const float y = c3[v] + part[v * 64 + lane] + s_b3[c];
+                        if (a.logits && row_ok) a.logits[(size_t)(row0 + r) * a.c + c] = y;
+                        if (best == kNoFlow || y > bv) {
+                            bv = y;
+                            best = c;
+                        }
                     }
                 }
+                // combine the two halves of the row: larger value wins, the lower class on a tie
+                const float ov = __shfl_xor(bv, 32, 64);
+                const uint32_t ob = (uint32_t)__shfl_xor((int)best, 32, 64);
+                if (ob != kNoFlow && (best == kNoFlow || ov > bv || (ov == bv && ob < best))) best = ob;
+                if (lane < 32u && row_ok) a.labels[flow_cur[r]] = (uint16_t)best;
             }
-            // combine the two halves of the row: larger value wins, the lower class on a tie
-            const float ov = __shfl_xor(bv, 32, 64);
-            const uint32_t ob = (uint32_t)__shfl_xor((int)best, 32, 64);
-            if (ob != 0xFFFFFFFFu && (best == 0xFFFFFFFFu || ov > bv || (ov == bv && ob < best))) best = ob;
-            if (lane < 32u && row_ok) a.labels[s_flow[r]] = (uint16_t)best;
         }
+        cur ^= 1u;
     }
 }
 
-constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + FBM * 4 + (2 * HMAX + 32) * 4;
+constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + 2 * FBM * 4 + (2 * HMAX + 32) * 4 + 4 * 16 * 64 * 4;
 
 } // namespace
 
@@ -327,7 +416,8 @@ bool slow_fused_ok(const sf_mlp* m, bool raw_input)
     return m->dtype == SF_BF16 && !raw_input && m->n_in <= HMAX && m->n_h1 <= HMAX && m->n_h2 <= HMAX && m->n_classes <= 32;
 }
 
-static size_t sw_bytes(uint32_t N, uint32_t K) { return align_up((size_t)(up(N, 32) / 32) * (up(K, 16) / 16) * 64 * 16); }
+// the kernel reads kRing k-steps past the end of a column block: keep that much padding behind the last one
+static size_t sw_bytes(uint32_t N, uint32_t K) { return align_up((size_t)(up(N, 32) / 32) * (up(K, kPadK) / 16) * 64 * 16 + (size_t)kRing * 1024); }
 
 size_t slow_fused_ws_bytes(const sf_mlp* m)
 {
@@ -351,7 +441,7 @@ int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const
                  {m->w2, m->n_h2, m->n_h1, up(m->n_h2, 32) / 32, w2s},
                  {m->w3, m->n_classes, m->n_h2, 1u, w3s}};
     for (auto& j : jobs) {
-        const uint32_t KS = up(j.K, 16) / 16, total = j.NB * KS * 64;
+        const uint32_t KS = up(j.K, kPadK) / 16, total = j.NB * KS * 64;
         uint32_t blocks = (total + 255) / 256;
         if (blocks > 4096) blocks = 4096;
         reorder_weights<<<blocks, 256, 0, ctx->stream>>>((const uint16_t*)j.w, j.N, j.K, j.NB, KS, j.out);
