@@ -132,18 +132,26 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
     for (int s = 0; s < kRing; ++s)
 #pragma unroll
         for (int j = 0; j < kNI; ++j) fb[s][j] = wl[j][s * 64 + lane];
+    // the activation operands are double-buffered too: those of k-step ks+1 are read from shared
+    // memory before the MFMAs of k-step ks are issued (H has 8 columns of padding, so the read
+    // one step past the end stays inside the row)
+    uint4 fa[2][kMI];
+#pragma unroll
+    for (int i = 0; i < kMI; ++i) fa[0][i] = *reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda);
     for (uint32_t k0 = 0; k0 < KS; k0 += kRing) {
 #pragma unroll
         for (int s = 0; s < kRing; ++s) {
-            bf16x8 fa[kMI];
+            const uint32_t kn = k0 + s + 1u < KS ? k0 + s + 1u : k0 + s;
 #pragma unroll
             for (int i = 0; i < kMI; ++i)
-                fa[i] = as_frag(*reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda + (k0 + s) * 16u));
+                fa[(s + 1) & 1][i] = *reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda + kn * 16u);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < kNI; ++j) {
                 const bf16x8 b = as_frag(fb[s][j]);
 #pragma unroll
-                for (int i = 0; i < kMI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[i], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < kMI; ++i)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, as_frag(fa[s & 1][i]), acc[i][j], 0, 0, 0);
             }
             // refill for k-step k0 + s + kRing; past the end this reads the next block (or the
             // padding behind the last one) and is never used
@@ -156,28 +164,22 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
     }
 }
 
-// H[row][col] = bfloat16(relu(acc + bias)) for the wave's columns.  Columns in [n_valid, n_pad) come out as
-// zeros by themselves: their weights and their (shared-memory) bias entries are zero.
-__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], const float* sbias,
-                                             uint32_t n0, uint32_t n_valid, uint32_t n_pad, uint32_t lane)
+// H[row][col] = bfloat16(relu(acc)) for the wave's columns (the bias is already in acc).  Columns in
+// [n_valid, n_pad) come out as zeros by themselves: their weights and their bias entries are zero.
+__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], uint32_t n0, uint32_t n_pad,
+                                             uint32_t lane)
 {
-    (void)n_valid;
 #pragma unroll
     for (int j = 0; j < kNI; ++j) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5); // first of 4 consecutive columns
             if (col < n_pad) {
-                const float4 b = *reinterpret_cast<const float4*>(sbias + col);
 #pragma unroll
                 for (int i = 0; i < kMI; ++i) {
                     const uint32_t row = i * 32u + (lane & 31u);
-                    float y0 = acc[i][j][4 * g + 0] + b.x, y1 = acc[i][j][4 * g + 1] + b.y;
-                    float y2 = acc[i][j][4 * g + 2] + b.z, y3 = acc[i][j][4 * g + 3] + b.w;
-                    y0 = y0 > 0.f ? y0 : 0.f;
-                    y1 = y1 > 0.f ? y1 : 0.f;
-                    y2 = y2 > 0.f ? y2 : 0.f;
-                    y3 = y3 > 0.f ? y3 : 0.f;
+                    const float y0 = fmaxf(acc[i][j][4 * g + 0], 0.f), y1 = fmaxf(acc[i][j][4 * g + 1], 0.f);
+                    const float y2 = fmaxf(acc[i][j][4 * g + 2], 0.f), y3 = fmaxf(acc[i][j][4 * g + 3], 0.f);
                     *reinterpret_cast<uint2*>(H + row * LDH + col) = make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3));
                 }
             }
@@ -185,14 +187,24 @@ __device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kM
     }
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[kMI][kNI])
+// accumulators start at the bias of their column (element v of lane l is column
+// 8*(v/4) + 4*(l/32) + v%4 of the 32-column block), so the epilogue has no add
+__device__ __forceinline__ void bias_acc(f32x16 (&acc)[kMI][kNI], const float* sbias, uint32_t n0, uint32_t lane)
 {
 #pragma unroll
-    for (int i = 0; i < kMI; ++i)
+    for (int j = 0; j < kNI; ++j)
 #pragma unroll
-        for (int j = 0; j < kNI; ++j)
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5);
+            const float4 b = col < (uint32_t)HMAX ? *reinterpret_cast<const float4*>(sbias + col) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int i = 0; i < kMI; ++i) {
+                acc[i][j][4 * g + 0] = b.x;
+                acc[i][j][4 * g + 1] = b.y;
+                acc[i][j][4 * g + 2] = b.z;
+                acc[i][j][4 * g + 3] = b.w;
+            }
+        }
 }
 
 constexpr uint32_t kNoFlow = 0xFFFFFFFFu;
@@ -216,17 +228,21 @@ __device__ __forceinline__ void load_chunk(const FusedArgs& a, uint32_t flow, ui
 }
 
 // standardise, clamp, round to bfloat16 and store one chunk of the input tile
-__device__ __forceinline__ void store_chunk(const FusedArgs& a, uint16_t* dst, uint32_t k, float (&z)[8])
+// (s_mu / s_is: the input map in shared memory, zero / one past n_in; has_map false = identity)
+__device__ __forceinline__ void store_chunk(bool has_map, const float* s_mu, const float* s_is, float clamp,
+                                            uint16_t* dst, uint32_t k, float (&z)[8])
 {
-    if (a.mu) {
+    if (has_map) {
+        const float4 m0 = *reinterpret_cast<const float4*>(s_mu + k), m1 = *reinterpret_cast<const float4*>(s_mu + k + 4);
+        const float4 i0 = *reinterpret_cast<const float4*>(s_is + k), i1 = *reinterpret_cast<const float4*>(s_is + k + 4);
+        const float mu[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+        const float is[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            if (k + q < a.n_in) {
-                const float d = z[q] - a.mu[k + q];
-                float t = d * a.inv_sigma[k + q];
-                t = t < -a.clamp ? -a.clamp : t;
-                z[q] = t > a.clamp ? a.clamp : t;
-            }
+            const float d = z[q] - mu[q];
+            float t = d * is[q];
+            t = t < -clamp ? -clamp : t;
+            z[q] = t > clamp ? clamp : t;
         }
     }
     *reinterpret_cast<uint4*>(dst) =
@@ -249,6 +265,8 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
     float* s_b2 = s_b1 + HMAX;                                                     // [HMAX], zero past h2
     float* s_b3 = s_b2 + HMAX;                                                     // [32], zero past c
     float* s_part = s_b3 + 32;                                                     // [4][16][64] last-layer partial sums
+    float* s_mu = s_part + 4 * 16 * 64;                                            // [HMAX] input map (0 / 1 if none)
+    float* s_is = s_mu + HMAX;                                                     // [HMAX]
     // the wave index is the same in every lane: say so, and everything derived from it (column
     // block, weight pointers) lives in scalar registers
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -267,7 +285,10 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
         s_b1[q] = q < a.h1 ? a.b1[q] : 0.f;
         s_b2[q] = q < a.h2 ? a.b2[q] : 0.f;
         if (q < 32u) s_b3[q] = q < a.c ? a.b3[q] : 0.f;
+        s_mu[q] = (a.mu && q < a.n_in) ? a.mu[q] : 0.f;
+        s_is[q] = (a.mu && q < a.n_in) ? a.inv_sigma[q] : 1.f;
     }
+    const bool has_map = a.mu != nullptr;
     float xr[kXr][8];
     {
         // first tile: flow ids and feature rows are fetched here, with nothing to overlap them
@@ -302,31 +323,31 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
 #pragma unroll
             for (int u = 0; u < kXr; ++u) {
                 const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
-                if (r < (uint32_t)FBM) store_chunk(a, H + r * ldx + k, k, xr[u]);
+                if (r < (uint32_t)FBM) store_chunk(has_map, s_mu, s_is, a.clamp, H + r * ldx + k, k, xr[u]);
             }
         } else {
             for (uint32_t g = tid; g < FBM * chunks; g += kWaves * 64u) {
                 const uint32_t r = g / chunks, k = (g - r * chunks) * 8u;
                 float z[8];
                 load_chunk(a, flow_cur[r], k, z);
-                store_chunk(a, H + r * ldx + k, k, z);
+                store_chunk(has_map, s_mu, s_is, a.clamp, H + r * ldx + k, k, z);
             }
         }
         __syncthreads();
 
         f32x16 acc[kMI][kNI];
         // layer 1
-        zero_acc(acc);
+        bias_acc(acc, s_b1, n0, lane);
         wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc);
         __syncthreads(); // every wave has read the input tile; H may be overwritten
         if (tid < FBM) flow_next[tid] = nf;
-        store_hidden(H, acc, s_b1, n0, a.h1, k2p, lane);
+        store_hidden(H, acc, n0, k2p, lane);
         __syncthreads();
         // layer 2
-        zero_acc(acc);
+        bias_acc(acc, s_b2, n0, lane);
         wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc);
         __syncthreads();
-        store_hidden(H, acc, s_b2, n0, a.h2, k3p, lane);
+        store_hidden(H, acc, n0, k3p, lane);
         // layer 3: wave = (row block rb, half kh of K).  The hidden accumulators are dead, so a
         // whole half-layer of weight operands fits in registers; they are requested before the
         // barrier so that their latency overlaps it.
@@ -405,7 +426,7 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
     }
 }
 
-constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + 2 * FBM * 4 + (2 * HMAX + 32) * 4 + 4 * 16 * 64 * 4;
+constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + 2 * FBM * 4 + (4 * HMAX + 32) * 4 + 4 * 16 * 64 * 4;
 
 } // namespace
 
