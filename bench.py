@@ -24,15 +24,6 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 F32_VECTOR_PEAK_TFLOPS = 157.3
 
 
-def pick_vmin(top_votes: np.ndarray, n_trees: int, target: float):
-    """Target-portion rule of Section 3.2 on an integer score: the threshold whose escalated fraction
-    is nearest the target (ties -> the smaller fraction).  Host-side calibration, outside the timing."""
-    hist = np.bincount(top_votes, minlength=n_trees + 2).astype(np.float64)
-    below = np.concatenate([[0.0], np.cumsum(hist)])[: n_trees + 2] / top_votes.size   # frac with top < v
-    best = min(range(n_trees + 2), key=lambda v: (abs(below[v] - target), below[v]))
-    return best, float(below[best])
-
-
 def algorithmic_bytes(cfg, n_flows, n_pkts, esc_frac):
     """Bytes the method itself must move per call (inputs read once + outputs written once)."""
     F = cfg.n_features
@@ -119,18 +110,19 @@ def main():
     ctx.sf_validate_forest(d_forest)
 
     # gate threshold: explicit, from theta, or the target-portion rule on this run's own scores
+    # (target-portion rule of Section 3.2: the library histograms the integer score on the device and
+    # picks the threshold whose escalated fraction is nearest the target; outside the timed region)
     ctx.sf_fast_infer(feat, d_forest, pred, top)
-    torch.cuda.synchronize()
-    top_h = top.cpu().numpy().view(np.uint16)
+    hist = ctx.sf_score_histogram(top, cfg.n_trees)
     if args.target >= 0:
-        vmin, frac = pick_vmin(top_h, cfg.n_trees, args.target)
+        vmin, _ = sf.sf_vmin_for_target(hist, cfg.n_trees, args.target)
     elif cfg.vmin is not None:
         vmin = cfg.vmin
     elif cfg.theta is not None:
         vmin = sf.sf_vmin_from_theta(cfg.theta, cfg.n_trees)
     else:
-        vmin, frac = pick_vmin(top_h, cfg.n_trees, cfg.target_fracs[len(cfg.target_fracs) // 2])
-    frac = float((top_h < vmin).mean())
+        vmin, _ = sf.sf_vmin_for_target(hist, cfg.n_trees, cfg.target_fracs[len(cfg.target_fracs) // 2])
+    frac = sum(hist[:vmin]) / float(n)
     esc_cap = n
 
     def step(ev=None):

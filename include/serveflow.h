@@ -155,6 +155,28 @@ int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint3
 /* ceil(theta * n_trees), exact for theta's binary32 value, clamped to 0..65535.  Host. */
 uint32_t sf_vmin_from_theta(float theta, uint32_t n_trees);
 
+/* ---- threshold calibration (Section 3.2, Algorithm 1 and "Determining the optimal threshold") ----
+ * The uncertainty score here takes only n_trees+1 values, so its sorted list is a histogram.
+ *
+ * sf_score_histogram: host_hist[v] (v = 0..n_trees, n_trees+1 words, HOST memory) = number of flows
+ * with top_votes == v (device array, [n_flows]).  Runs on the device, then waits for the stream. */
+int sf_score_histogram(sf_ctx* ctx, const uint16_t* top_votes, uint32_t n_flows, uint32_t n_trees,
+                       uint32_t* host_hist);
+
+/* Algorithm 1 (universal uncertainty thresholds) on that histogram: sort the scores
+ * LC = 1 - top_votes/n_trees ascending and, for each quantile q, take the element at 1-based
+ * position ceil(q * n) (position 0 is read as 1).  host_votes_at[j] receives the top_votes value v
+ * of that element, i.e. the threshold is LC = 1 - v/n_trees; escalating the flows with LC above it
+ * is the gate vmin = v, which assigns at most a fraction 1 - q of the flows.  Host function. */
+int sf_universal_thresholds(const uint32_t* host_hist, uint32_t n_trees, const double* host_q, uint32_t n_q,
+                            uint16_t* host_votes_at);
+
+/* The "target portion" way of fixing the threshold: the vmin (0..n_trees+1) whose escalated
+ * fraction (flows with top_votes < vmin) is nearest target_fraction; on a tie the smaller fraction.
+ * *reached_fraction (optional) receives the fraction actually reached.  Host function. */
+uint32_t sf_vmin_for_target(const uint32_t* host_hist, uint32_t n_trees, double target_fraction,
+                            double* reached_fraction);
+
 /* ---- step 5: slow model on the escalated flows only ------------------------------------
  * Sections 3.1 and 4.4: only flows the fast model is unsure of reach the slow model, and
  * its answer replaces the fast one.  The slow model is a 3-layer ReLU MLP.

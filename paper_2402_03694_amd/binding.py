@@ -20,7 +20,8 @@ SF_MAX_WINDOWS = 4
 
 EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf_featurize",
            "sf_validate_packets", "sf_fast_infer", "sf_validate_forest", "sf_route",
-           "sf_vmin_from_theta", "sf_slow_infer")
+           "sf_vmin_from_theta", "sf_slow_infer", "sf_score_histogram", "sf_universal_thresholds",
+           "sf_vmin_for_target")
 
 
 class SfPackets(ctypes.Structure):
@@ -85,6 +86,14 @@ def load_library() -> ctypes.CDLL:
     lib.sf_slow_infer.restype = ctypes.c_int
     lib.sf_slow_infer.argtypes = [vp, vp, u32, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), vp, vp,
                                   u32, u32, ctypes.POINTER(SfMlp), vp, vp, vp]
+    lib.sf_score_histogram.restype = ctypes.c_int
+    lib.sf_score_histogram.argtypes = [vp, vp, u32, u32, ctypes.POINTER(ctypes.c_uint32)]
+    lib.sf_universal_thresholds.restype = ctypes.c_int
+    lib.sf_universal_thresholds.argtypes = [ctypes.POINTER(ctypes.c_uint32), u32, ctypes.POINTER(ctypes.c_double), u32,
+                                            ctypes.POINTER(ctypes.c_uint16)]
+    lib.sf_vmin_for_target.restype = u32
+    lib.sf_vmin_for_target.argtypes = [ctypes.POINTER(ctypes.c_uint32), u32, ctypes.c_double,
+                                       ctypes.POINTER(ctypes.c_double)]
     return lib
 
 
@@ -116,6 +125,25 @@ def sf_workspace_bytes(max_flows: int, n_trees: int = 0, tree_depth: int = 0, n_
 
 def sf_vmin_from_theta(theta: float, n_trees: int) -> int:
     return int(lib().sf_vmin_from_theta(ctypes.c_float(theta), n_trees))
+
+
+def sf_universal_thresholds(hist, n_trees: int, quantiles):
+    """hist: sequence of n_trees+1 counts.  Returns the top_votes value at each quantile (Algorithm 1)."""
+    h = (ctypes.c_uint32 * (n_trees + 1))(*[int(x) for x in hist])
+    q = (ctypes.c_double * len(quantiles))(*[float(x) for x in quantiles])
+    out = (ctypes.c_uint16 * len(quantiles))()
+    rc = lib().sf_universal_thresholds(h, n_trees, q, len(quantiles), out)
+    if rc != SF_OK:
+        raise ServeFlowError(rc, "sf_universal_thresholds: bad arguments or empty histogram")
+    return list(out)
+
+
+def sf_vmin_for_target(hist, n_trees: int, target: float):
+    """Returns (vmin, reached escalated fraction)."""
+    h = (ctypes.c_uint32 * (n_trees + 1))(*[int(x) for x in hist])
+    reached = ctypes.c_double()
+    v = lib().sf_vmin_for_target(h, n_trees, float(target), ctypes.byref(reached))
+    return int(v), float(reached.value)
 
 
 class DevicePackets:
@@ -253,6 +281,12 @@ class ServeFlow:
         n = int(top_votes.shape[0]) if n_flows is None else n_flows
         self._check(self._lib.sf_route(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr, len(vm),
                                        _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_score_histogram(self, top_votes: torch.Tensor, n_trees: int, n_flows: Optional[int] = None):
+        n = int(top_votes.shape[0]) if n_flows is None else n_flows
+        hist = (ctypes.c_uint32 * (n_trees + 1))()
+        self._check(self._lib.sf_score_histogram(self._h, _ptr(top_votes, torch.int16), n, n_trees, hist))
+        return list(hist)
 
     def sf_slow_infer(self, mlp: DeviceMlp, esc_idx: torch.Tensor, esc_count: torch.Tensor, labels: torch.Tensor,
                       feat: Optional[torch.Tensor] = None, raw_src: Optional[DevicePackets] = None,

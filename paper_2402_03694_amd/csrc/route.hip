@@ -5,6 +5,8 @@
 // block's contiguous chunk; the second adds up the counts of the blocks before it, then
 // re-evaluates the gate and writes the indices in order (a wave-level prefix sum of per-lane
 // pop-counts gives each lane its write position).  The count stays on the device.
+#include <cmath>
+
 #include "common.h"
 
 namespace {
@@ -136,6 +138,40 @@ __global__ __launch_bounds__(kBlock) void route_scatter(RouteArgs a)
 
 __global__ void route_zero(uint32_t* esc_count) { *esc_count = 0; }
 
+// ---- calibration: histogram of the integer score ------------------------------------------
+
+constexpr uint32_t kHistLdsBins = 8192; // bins a block can keep in shared memory (32 KB)
+
+__global__ __launch_bounds__(256) void hist_zero(uint32_t* hist, uint32_t bins)
+{
+    for (uint32_t b = blockIdx.x * blockDim.x + threadIdx.x; b < bins; b += gridDim.x * blockDim.x) hist[b] = 0;
+}
+
+// hist[v] += number of flows with top_votes == v (values above n_trees are counted in the last bin)
+__global__ __launch_bounds__(256) void hist_scores(const uint16_t* __restrict__ top, uint32_t n, uint32_t bins,
+                                                   uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t sh[kHistLdsBins];
+    const bool local = bins <= kHistLdsBins;
+    if (local) {
+        for (uint32_t b = threadIdx.x; b < bins; b += blockDim.x) sh[b] = 0;
+        __syncthreads();
+    }
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        uint32_t v = top[i];
+        v = v < bins ? v : bins - 1u;
+        if (local)
+            atomicAdd(&sh[v], 1u);
+        else
+            atomicAdd(&hist[v], 1u);
+    }
+    if (local) {
+        __syncthreads();
+        for (uint32_t b = threadIdx.x; b < bins; b += blockDim.x)
+            if (sh[b]) atomicAdd(&hist[b], sh[b]);
+    }
+}
+
 } // namespace
 
 extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
@@ -178,4 +214,81 @@ extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* 
     route_scatter<<<grid, kBlock, 0, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "route_scatter");
     return SF_OK;
+}
+
+// ---- calibration entry points ------------------------------------------------------------------
+
+extern "C" int sf_score_histogram(sf_ctx* ctx, const uint16_t* top_votes, uint32_t n_flows, uint32_t n_trees,
+                                  uint32_t* host_hist)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_score_histogram: ctx is NULL");
+    if (!host_hist) return sf::fail(ctx, SF_EINVAL, "sf_score_histogram: host_hist is NULL");
+    if (n_trees < 1 || n_trees > 65535) return sf::fail(ctx, SF_EINVAL, "sf_score_histogram: n_trees %u outside 1..65535", n_trees);
+    const uint32_t bins = n_trees + 1u;
+    if (n_flows == 0) {
+        for (uint32_t b = 0; b < bins; ++b) host_hist[b] = 0;
+        return SF_OK;
+    }
+    if (!top_votes) return sf::fail(ctx, SF_EINVAL, "sf_score_histogram: top_votes is NULL");
+    sf::Carve ws(ctx);
+    uint32_t* d_hist = (uint32_t*)ws.take((size_t)bins * 4);
+    if (!d_hist) return sf::fail(ctx, SF_ENOMEM, "sf_score_histogram: workspace too small for %u bins", bins);
+    hist_zero<<<(bins + 255) / 256, 256, 0, ctx->stream>>>(d_hist, bins);
+    SF_LAUNCH_CHECK(ctx, "hist_zero");
+    uint32_t blocks = (n_flows + 256 * 16 - 1) / (256 * 16);
+    blocks = blocks > 2048 ? 2048 : blocks;
+    hist_scores<<<blocks, 256, 0, ctx->stream>>>(top_votes, n_flows, bins, d_hist);
+    SF_LAUNCH_CHECK(ctx, "hist_scores");
+    SF_HIP(ctx, hipMemcpyAsync(host_hist, d_hist, (size_t)bins * 4, hipMemcpyDeviceToHost, ctx->stream));
+    SF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return SF_OK;
+}
+
+extern "C" int sf_universal_thresholds(const uint32_t* host_hist, uint32_t n_trees, const double* host_q, uint32_t n_q,
+                                       uint16_t* host_votes_at)
+{
+    if (!host_hist || !host_q || !host_votes_at || n_trees < 1 || n_trees > 65535) return SF_EINVAL;
+    uint64_t n = 0;
+    for (uint32_t v = 0; v <= n_trees; ++v) n += host_hist[v];
+    if (n == 0) return SF_EINVAL;
+    for (uint32_t j = 0; j < n_q; ++j) {
+        // 1-based position ceil(q * n) in the ascending order of LC = descending order of top_votes
+        double pos = std::ceil(host_q[j] * (double)n);
+        if (!(pos >= 1.0)) pos = 1.0;
+        if (pos > (double)n) pos = (double)n;
+        const uint64_t want = (uint64_t)pos;
+        uint64_t seen = 0;
+        uint32_t v = n_trees;
+        for (;; --v) {
+            seen += host_hist[v];
+            if (seen >= want || v == 0) break;
+        }
+        host_votes_at[j] = (uint16_t)v;
+    }
+    return SF_OK;
+}
+
+extern "C" uint32_t sf_vmin_for_target(const uint32_t* host_hist, uint32_t n_trees, double target_fraction,
+                                       double* reached_fraction)
+{
+    if (!host_hist || n_trees < 1 || n_trees > 65535) return 0;
+    uint64_t n = 0;
+    for (uint32_t v = 0; v <= n_trees; ++v) n += host_hist[v];
+    uint32_t best = 0;
+    uint64_t best_below = 0, below = 0; // below = flows with top_votes < vmin
+    // |below/n - target| compared exactly as |below - target*n| (same double product for every candidate)
+    const double tn = target_fraction * (double)n;
+    double best_d = tn < 0 ? -tn : tn;
+    for (uint32_t vmin = 1; vmin <= n_trees + 1u; ++vmin) {
+        below += host_hist[vmin - 1];
+        double d = (double)below - tn;
+        d = d < 0 ? -d : d;
+        if (d < best_d) { // strict: on a tie the smaller fraction (found first) stays
+            best_d = d;
+            best = vmin;
+            best_below = below;
+        }
+    }
+    if (reached_fraction) *reached_fraction = n ? (double)best_below / (double)n : 0.0;
+    return best;
 }

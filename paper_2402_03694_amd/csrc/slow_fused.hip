@@ -72,18 +72,31 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 u)
 
 // W[N][K] (row-major, bfloat16 bits) -> out[(nb * KS + ks) * 64 + lane] = the 8 values
 // W[nb*32 + lane%32][ks*16 + 8*(lane/32) .. +8), zero outside; nb < NB, ks < KS.
-__global__ __launch_bounds__(256) void reorder_weights(const uint16_t* __restrict__ w, uint32_t N, uint32_t K, uint32_t NB,
-                                                       uint32_t KS, uint4* __restrict__ out)
+// One launch re-orders all three layers.
+struct ReorderJob {
+    const uint16_t* w;
+    uint32_t N, K, NB, KS;
+    uint32_t first; // index of the job's first 16-byte element in the launch-wide numbering
+    uint4* out;
+};
+struct ReorderArgs {
+    ReorderJob job[3];
+    uint32_t total;
+};
+
+__global__ __launch_bounds__(256) void reorder_weights(ReorderArgs r)
 {
-    const uint32_t total = NB * KS * 64u;
-    for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < total; g += gridDim.x * blockDim.x) {
-        const uint32_t lane = g & 63u, t = g >> 6, ks = t % KS, nb = t / KS;
+    for (uint32_t e = blockIdx.x * blockDim.x + threadIdx.x; e < r.total; e += gridDim.x * blockDim.x) {
+        const int ji = e >= r.job[2].first ? 2 : (e >= r.job[1].first ? 1 : 0);
+        const ReorderJob& jb = r.job[ji];
+        const uint32_t g = e - jb.first;
+        const uint32_t lane = g & 63u, t = g >> 6, ks = t % jb.KS, nb = t / jb.KS;
         const uint32_t n = nb * 32u + (lane & 31u), k0 = ks * 16u + 8u * (lane >> 5);
         uint16_t v[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = (n < N && k0 + q < K) ? w[(size_t)n * K + k0 + q] : (uint16_t)0;
-        out[g] = make_uint4(v[0] | ((uint32_t)v[1] << 16), v[2] | ((uint32_t)v[3] << 16), v[4] | ((uint32_t)v[5] << 16),
-                            v[6] | ((uint32_t)v[7] << 16));
+        for (int q = 0; q < 8; ++q) v[q] = (n < jb.N && k0 + q < jb.K) ? jb.w[(size_t)n * jb.K + k0 + q] : (uint16_t)0;
+        jb.out[g] = make_uint4(v[0] | ((uint32_t)v[1] << 16), v[2] | ((uint32_t)v[3] << 16), v[4] | ((uint32_t)v[5] << 16),
+                               v[6] | ((uint32_t)v[7] << 16));
     }
 }
 
@@ -454,18 +467,26 @@ int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const
     uint4* w2s = (uint4*)p;
     p += sw_bytes(m->n_h2, m->n_h1);
     uint4* w3s = (uint4*)p;
-    struct {
-        const void* w;
-        uint32_t N, K, NB;
-        uint4* out;
-    } jobs[3] = {{m->w1, m->n_h1, m->n_in, up(m->n_h1, 32) / 32, w1s},
-                 {m->w2, m->n_h2, m->n_h1, up(m->n_h2, 32) / 32, w2s},
-                 {m->w3, m->n_classes, m->n_h2, 1u, w3s}};
-    for (auto& j : jobs) {
-        const uint32_t KS = up(j.K, kPadK) / 16, total = j.NB * KS * 64;
-        uint32_t blocks = (total + 255) / 256;
+    ReorderArgs r;
+    const void* ws_in[3] = {m->w1, m->w2, m->w3};
+    const uint32_t Ns[3] = {m->n_h1, m->n_h2, m->n_classes}, Ks[3] = {m->n_in, m->n_h1, m->n_h2};
+    const uint32_t NBs[3] = {up(m->n_h1, 32) / 32, up(m->n_h2, 32) / 32, 1u};
+    uint4* outs[3] = {w1s, w2s, w3s};
+    r.total = 0;
+    for (int q = 0; q < 3; ++q) {
+        r.job[q].w = (const uint16_t*)ws_in[q];
+        r.job[q].N = Ns[q];
+        r.job[q].K = Ks[q];
+        r.job[q].NB = NBs[q];
+        r.job[q].KS = up(Ks[q], kPadK) / 16;
+        r.job[q].first = r.total;
+        r.job[q].out = outs[q];
+        r.total += NBs[q] * r.job[q].KS * 64;
+    }
+    {
+        uint32_t blocks = (r.total + 255) / 256;
         if (blocks > 4096) blocks = 4096;
-        reorder_weights<<<blocks, 256, 0, ctx->stream>>>((const uint16_t*)j.w, j.N, j.K, j.NB, KS, j.out);
+        reorder_weights<<<blocks, 256, 0, ctx->stream>>>(r);
         SF_LAUNCH_CHECK(ctx, "reorder_weights");
     }
     FusedArgs a;
