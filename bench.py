@@ -90,7 +90,7 @@ def main():
     n_pkts = pk.n_pkts
     F, C = cfg.n_features, cfg.n_classes
     h1, h2 = cfg.mlp_dims[1], cfg.mlp_dims[2]
-    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, h1, h2))
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, cfg.mlp_dims[0], h1, h2))
     d_pk = sf.packets_to_device(pk, dev)
     feat = torch.empty((n, F), dtype=torch.float32, device=dev)
     pred = torch.empty(n, dtype=torch.int16, device=dev)

@@ -57,10 +57,10 @@ enum { SF_F32 = 0, SF_BF16 = 1 };
 /* ---- context ------------------------------------------------------------------------ */
 
 /* Scratch bytes that cover every entry point for at most max_flows flows per call, a
- * forest of n_trees trees of depth tree_depth and an MLP with hidden widths n_h1, n_h2
+ * forest of n_trees trees of depth tree_depth and an MLP n_in -> n_h1 -> n_h2 -> classes
  * (pass zeros for the parts not used).  Host function, no GPU needed. */
 size_t sf_workspace_bytes(uint32_t max_flows, uint32_t n_trees, uint32_t tree_depth,
-                          uint32_t n_h1, uint32_t n_h2);
+                          uint32_t n_in, uint32_t n_h1, uint32_t n_h2);
 
 /* Create a context bound to hip_stream (a hipStream_t; NULL = the default stream) and to
  * a caller-owned device workspace of workspace_bytes bytes (256-byte aligned).  The

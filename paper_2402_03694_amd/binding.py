@@ -64,7 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     vp, u32, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_size_t
     lib.sf_workspace_bytes.restype = sz
-    lib.sf_workspace_bytes.argtypes = [u32] * 5
+    lib.sf_workspace_bytes.argtypes = [u32] * 6
     lib.sf_create.restype = ctypes.c_int
     lib.sf_create.argtypes = [ctypes.POINTER(vp), vp, vp, sz]
     lib.sf_destroy.restype = None
@@ -119,8 +119,9 @@ def _ptr(t: Optional[torch.Tensor], dtype=None):
     return ctypes.c_void_p(t.data_ptr())
 
 
-def sf_workspace_bytes(max_flows: int, n_trees: int = 0, tree_depth: int = 0, n_h1: int = 0, n_h2: int = 0) -> int:
-    return int(lib().sf_workspace_bytes(max_flows, n_trees, tree_depth, n_h1, n_h2))
+def sf_workspace_bytes(max_flows: int, n_trees: int = 0, tree_depth: int = 0, n_in: int = 0, n_h1: int = 0,
+                       n_h2: int = 0) -> int:
+    return int(lib().sf_workspace_bytes(max_flows, n_trees, tree_depth, n_in, n_h1, n_h2))
 
 
 def sf_vmin_from_theta(theta: float, n_trees: int) -> int:

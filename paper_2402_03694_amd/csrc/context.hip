@@ -43,14 +43,21 @@ size_t slow_row_bytes(uint32_t n_h1, uint32_t n_h2, int dtype)
 
 } // namespace sf
 
+namespace sf {
+size_t reordered_bytes(uint32_t N, uint32_t K); // slow_fused.hip
+}
+
 extern "C" size_t sf_workspace_bytes(uint32_t max_flows, uint32_t n_trees, uint32_t tree_depth,
-                                     uint32_t n_h1, uint32_t n_h2)
+                                     uint32_t n_in, uint32_t n_h1, uint32_t n_h2)
 {
     using namespace sf;
     size_t total = kFlagBytes;
     total = align_up(total) + forest_pack_bytes(n_trees, tree_depth);
     total = align_up(total) + route_scratch_bytes(max_flows);
     if (n_h1 || n_h2) {
+        // operand-ordered copies of the three weight matrices
+        total = align_up(total) + reordered_bytes(n_h1, n_in ? n_in : 1) + reordered_bytes(n_h2, n_h1 ? n_h1 : 1) +
+                reordered_bytes(32, n_h2 ? n_h2 : 1) + 4 * kAlign;
         uint32_t rows = max_flows < kSlowWantRows ? max_flows : kSlowWantRows;
         if (rows < kSlowMinRows) rows = kSlowMinRows;
         total = align_up(total) + align_up((size_t)rows * slow_row_bytes(n_h1, n_h2, SF_F32)) + 2 * kAlign;

@@ -13,7 +13,7 @@
 // each of four waves, followed by a per-row arg-max in registers and the scatter of the label.
 // Blocks are persistent: each walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... up to the
 // device-side escalation count, so no block is launched for rows that do not exist.
-#include "common.h"
+#include "mlp_common.h"
 
 namespace sf {
 bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
@@ -458,6 +458,32 @@ size_t slow_fused_ws_bytes(const sf_mlp* m)
     return sw_bytes(m->n_h1, m->n_in) + sw_bytes(m->n_h2, m->n_h1) + sw_bytes(32, m->n_h2) + 3 * kAlign;
 }
 
+size_t reordered_bytes(uint32_t N, uint32_t K) { return sw_bytes(N, K); }
+
+int reorder_weights_async(sf_ctx* ctx, const ReorderSpec* specs, int n_specs)
+{
+    if (n_specs < 1 || n_specs > 3) return fail(ctx, SF_EINVAL, "reorder_weights_async: 1..3 matrices per launch");
+    ReorderArgs r;
+    r.total = 0;
+    for (int q = 0; q < 3; ++q) {
+        const ReorderSpec& sp = specs[q < n_specs ? q : n_specs - 1];
+        r.job[q].w = (const uint16_t*)sp.w;
+        r.job[q].N = sp.N;
+        r.job[q].K = sp.K;
+        r.job[q].NB = up(sp.N, 32) / 32;
+        r.job[q].KS = up(sp.K, kPadK) / 16;
+        r.job[q].first = r.total;
+        r.job[q].out = (uint4*)sp.out;
+        if (q < n_specs) r.total += r.job[q].NB * r.job[q].KS * 64;
+    }
+    // jobs past n_specs start at r.total, so no element maps to them
+    uint32_t blocks = (r.total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    reorder_weights<<<blocks, 256, 0, ctx->stream>>>(r);
+    SF_LAUNCH_CHECK(ctx, "reorder_weights");
+    return SF_OK;
+}
+
 int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
                const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* m, float* logits, uint16_t* labels)
 {
@@ -467,27 +493,11 @@ int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const
     uint4* w2s = (uint4*)p;
     p += sw_bytes(m->n_h2, m->n_h1);
     uint4* w3s = (uint4*)p;
-    ReorderArgs r;
-    const void* ws_in[3] = {m->w1, m->w2, m->w3};
-    const uint32_t Ns[3] = {m->n_h1, m->n_h2, m->n_classes}, Ks[3] = {m->n_in, m->n_h1, m->n_h2};
-    const uint32_t NBs[3] = {up(m->n_h1, 32) / 32, up(m->n_h2, 32) / 32, 1u};
-    uint4* outs[3] = {w1s, w2s, w3s};
-    r.total = 0;
-    for (int q = 0; q < 3; ++q) {
-        r.job[q].w = (const uint16_t*)ws_in[q];
-        r.job[q].N = Ns[q];
-        r.job[q].K = Ks[q];
-        r.job[q].NB = NBs[q];
-        r.job[q].KS = up(Ks[q], kPadK) / 16;
-        r.job[q].first = r.total;
-        r.job[q].out = outs[q];
-        r.total += NBs[q] * r.job[q].KS * 64;
-    }
+    const ReorderSpec specs[3] = {{m->w1, m->n_h1, m->n_in, w1s}, {m->w2, m->n_h2, m->n_h1, w2s},
+                                  {m->w3, m->n_classes, m->n_h2, w3s}};
     {
-        uint32_t blocks = (r.total + 255) / 256;
-        if (blocks > 4096) blocks = 4096;
-        reorder_weights<<<blocks, 256, 0, ctx->stream>>>(r);
-        SF_LAUNCH_CHECK(ctx, "reorder_weights");
+        const int rc = reorder_weights_async(ctx, specs, 3);
+        if (rc != SF_OK) return rc;
     }
     FusedArgs a;
     a.esc_idx = esc_idx;

@@ -11,7 +11,7 @@
 // The row count comes from the device-side escalation count; blocks past it exit.
 //
 // binary32 models (small, used for the small workload) run on plain vector arithmetic.
-#include "common.h"
+#include "mlp_common.h"
 
 namespace sf {
 // fused single-kernel form for narrow hidden layers (slow_fused.hip)
@@ -19,143 +19,13 @@ bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
 size_t slow_fused_ws_bytes(const sf_mlp* mlp);
 int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
                const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* mlp, float* logits, uint16_t* labels);
+// one hidden layer of any width on operand-ordered weights (slow_wide.hip)
+int wide_layer(sf_ctx* ctx, int amode, const sfmlp::LayerArgs& a, const void* w_ordered, uint32_t rows_cap);
 } // namespace sf
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-constexpr int BM = 128; // rows per block
-constexpr int BK = 64;  // K per main-loop step
-constexpr int LDT = BK + 8; // shared-memory row stride (elements): 144 bytes keeps 16-byte
-                            // reads of 8 consecutive rows on distinct banks
-
-enum { A_BF16 = 0, A_FEAT = 1, A_RAW = 2 };
-
-struct LayerArgs {
-    // rows
-    const uint32_t* esc_idx;
-    const uint32_t* esc_count;
-    uint32_t esc_cap;
-    uint32_t row_begin; // first escalated row of this chunk
-    // A operand
-    const uint16_t* a_bf16; // [rows_in_chunk][lda]
-    uint32_t lda;
-    const float* feat;
-    uint32_t feat_ld;
-    const float* mu;
-    const float* inv_sigma;
-    float clamp;
-    const uint32_t* off;
-    const uint32_t* hdr;
-    uint32_t hdr_words, raw_bits, raw_pkts, n_pkts;
-    // weights
-    const uint16_t* w; // [N][K] bfloat16 bit patterns
-    const float* bias;
-    uint32_t N, K;
-    // output
-    uint16_t* h_out; // [rows_in_chunk][ldh] bfloat16
-    uint32_t ldh;
-    float* logits;   // [esc_cap][N] or NULL
-    uint16_t* labels;
-};
-
-__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16); // inf / nan: truncate
-    u += 0x7FFFu + ((u >> 16) & 1u);                                  // round to nearest even
-    return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
-
-// 8 consecutive K values [k, k+8) of escalated row e as bfloat16, zero past K.
-template <int AMODE>
-__device__ __forceinline__ uint4 load_a_chunk(const LayerArgs& a, bool row_ok, uint32_t row_in_chunk,
-                                              uint32_t flow, uint32_t k)
-{
-    uint4 out = make_uint4(0, 0, 0, 0);
-    if (!row_ok || k >= a.K) return out;
-    if (AMODE == A_BF16) {
-        const uint16_t* p = a.a_bf16 + (size_t)row_in_chunk * a.lda + k;
-        if (k + 8 <= a.K && (a.lda & 7u) == 0) return *reinterpret_cast<const uint4*>(p);
-        uint16_t v[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = k + q < a.K ? p[q] : (uint16_t)0;
-        return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-    }
-    if (AMODE == A_FEAT) {
-        const float* p = a.feat + (size_t)flow * a.feat_ld + k;
-        float x[8];
-        if (k + 8 <= a.K && (a.feat_ld & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.feat) & 15u) == 0 && (k & 3u) == 0) {
-            const float4 x0 = reinterpret_cast<const float4*>(p)[0], x1 = reinterpret_cast<const float4*>(p)[1];
-            x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w;
-            x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
-        } else {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) x[q] = k + q < a.K ? p[q] : 0.f;
-        }
-        uint16_t v[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            float z = x[q];
-            if (a.mu && k + q < a.K) {
-                const float d = z - a.mu[k + q];
-                z = d * a.inv_sigma[k + q];
-                z = z < -a.clamp ? -a.clamp : z;
-                z = z > a.clamp ? a.clamp : z;
-            }
-            v[q] = k + q < a.K ? f32_to_bf16_bits(z) : (uint16_t)0;
-        }
-        return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-    }
-    // A_RAW: feature k = raw_bits * packet + bit; bit b is bit 7-(b%8) of header byte b/8
-    uint32_t b0 = a.off[flow], e0 = a.off[flow + 1];
-    b0 = b0 < a.n_pkts ? b0 : a.n_pkts;
-    e0 = e0 < a.n_pkts ? e0 : a.n_pkts;
-    const uint32_t n = e0 > b0 ? e0 - b0 : 0;
-    uint16_t v[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const uint32_t kk = k + q;
-        uint16_t bit = 0;
-        if (kk < a.K) {
-            const uint32_t j = kk / a.raw_bits, b = kk - j * a.raw_bits;
-            if (j < n) {
-                const uint32_t byte_i = b >> 3;
-                const uint32_t word = a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)];
-                const uint32_t byte = (word >> (8u * (byte_i & 3u))) & 0xFFu;
-                bit = (uint16_t)((byte >> (7u - (b & 7u))) & 1u);
-            }
-        }
-        v[q] = bit ? (uint16_t)0x3F80 : (uint16_t)0; // bfloat16 1.0 or 0.0
-    }
-    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-}
-
-__device__ __forceinline__ uint4 load_w_chunk(const LayerArgs& a, uint32_t n, uint32_t k)
-{
-    if (n >= a.N || k >= a.K) return make_uint4(0, 0, 0, 0);
-    const uint16_t* p = a.w + (size_t)n * a.K + k;
-    if (k + 8 <= a.K && (a.K & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.w) & 15u) == 0)
-        return *reinterpret_cast<const uint4*>(p);
-    uint16_t v[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = k + q < a.K ? p[q] : (uint16_t)0;
-    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-}
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u)
-{
-    union {
-        uint4 u;
-        bf16x8 b;
-    } c;
-    c.u = u;
-    return c.b;
-}
+using namespace sfmlp;
 
 // One layer.  BN = columns per block; FINAL = last layer (logits, arg-max, label scatter).
 template <int AMODE, int BN, bool FINAL>
@@ -394,13 +264,6 @@ __global__ __launch_bounds__(256) void f32_argmax(const uint32_t* esc_idx, const
     }
 }
 
-template <int AMODE>
-void launch_hidden(sf_ctx* ctx, const LayerArgs& a, uint32_t rows_cap)
-{
-    dim3 grid((rows_cap + BM - 1) / BM, (a.ldh + 127) / 128);
-    mlp_layer<AMODE, 128, false><<<grid, 256, 0, ctx->stream>>>(a);
-}
-
 void launch_final(sf_ctx* ctx, const LayerArgs& a, uint32_t rows_cap)
 {
     dim3 grid((rows_cap + BM - 1) / BM, 1);
@@ -470,6 +333,16 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         return sf::slow_fused(ctx, w, feat, feat_ld, esc_idx, esc_count, esc_cap, mlp, logits, labels);
     }
     const bool bf = mlp->dtype == SF_BF16;
+    void *w1o = nullptr, *w2o = nullptr;
+    if (bf) {
+        // operand-ordered copies of the two hidden layers' weights
+        w1o = ws.take(sf::reordered_bytes(mlp->n_h1, mlp->n_in));
+        w2o = ws.take(sf::reordered_bytes(mlp->n_h2, mlp->n_h1));
+        if (!w1o || !w2o) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace too small for the re-ordered weights");
+        const sf::ReorderSpec specs[2] = {{mlp->w1, mlp->n_h1, mlp->n_in, w1o}, {mlp->w2, mlp->n_h2, mlp->n_h1, w2o}};
+        const int rc = sf::reorder_weights_async(ctx, specs, 2);
+        if (rc != SF_OK) return rc;
+    }
     const uint32_t ld1 = bf ? pad64(mlp->n_h1) : mlp->n_h1, ld2 = bf ? pad64(mlp->n_h2) : mlp->n_h2;
     const size_t row_bytes = bf ? ((size_t)ld1 + ld2) * 2 : ((size_t)mlp->n_in + ld1 + ld2 + mlp->n_classes) * 4;
     const size_t avail = ws.left() > 4 * sf::kAlign ? ws.left() - 4 * sf::kAlign : 0;
@@ -511,11 +384,10 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
             a.K = mlp->n_in;
             a.h_out = h1;
             a.ldh = ld1;
-            if (raw_src)
-                launch_hidden<A_RAW>(ctx, a, R);
-            else
-                launch_hidden<A_FEAT>(ctx, a, R);
-            SF_LAUNCH_CHECK(ctx, "mlp_layer 1");
+            {
+                const int rc = sf::wide_layer(ctx, raw_src ? A_RAW : A_FEAT, a, w1o, R);
+                if (rc != SF_OK) return rc;
+            }
             // layer 2
             a.a_bf16 = h1;
             a.lda = ld1;
@@ -525,8 +397,10 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
             a.K = mlp->n_h1;
             a.h_out = h2;
             a.ldh = ld2;
-            launch_hidden<A_BF16>(ctx, a, R);
-            SF_LAUNCH_CHECK(ctx, "mlp_layer 2");
+            {
+                const int rc = sf::wide_layer(ctx, A_BF16, a, w2o, R);
+                if (rc != SF_OK) return rc;
+            }
             // layer 3
             a.a_bf16 = h2;
             a.lda = ld2;

@@ -1,0 +1,200 @@
+// Step 5, one hidden layer of the slow model for any width (Sections 3.1 and 4.4 of the paper:
+// the slow model runs on the escalated flows only): H_out = relu(A * W^T + b), bfloat16 in,
+// binary32 MFMA accumulation, bfloat16 out.
+//
+// A block is eight waves and owns 128 rows x 512 output columns; wave w owns columns
+// [64w, 64w+64) for all 128 rows (4x2 accumulators of v_mfma_f32_32x32x16_bf16, weight operand
+// first, so a lane holds 4 consecutive columns of one row).  The A operand is streamed through
+// shared memory in slabs of 64 K-values, double-buffered, one barrier per slab; it is built by
+// the shared chunk loader (bfloat16 activations, gathered and standardised feature rows, or
+// unpacked header bits).  The weight operand comes operand-ordered straight from the cache
+// through a ring of register buffers, as in the fused kernel.  The output tile is staged in
+// shared memory (over the dead slabs) and written as whole 1 KB rows.
+#include "mlp_common.h"
+
+namespace sf {
+int wide_layer(sf_ctx* ctx, int amode, const sfmlp::LayerArgs& a, const void* w_ordered, uint32_t rows_cap);
+}
+
+namespace {
+
+using namespace sfmlp;
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+constexpr int WBM = 128;          // rows per block
+constexpr int WBN = 512;          // columns per block
+constexpr int WWAVES = 8;
+constexpr int WNI = 2, WMI = 4;   // 32-column / 32-row accumulator blocks per wave
+constexpr int WSLAB = 64;         // K values per slab
+constexpr int WLDS = WSLAB + 8;   // slab row stride (elements)
+constexpr int WLDO = WBN + 8;     // output tile row stride (elements)
+constexpr int WRING = 4;          // = k-steps per slab
+constexpr size_t kWideLds = (size_t)WBM * WLDO * 2 + WBM * 4; // output tile (covers both slabs) + flow ids
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    union {
+        bf16x2 b;
+        uint32_t u;
+    } c;
+    c.b = __builtin_convertvector(v, bf16x2);
+    return c.u;
+}
+
+template <int AMODE>
+__global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const uint4* __restrict__ ws)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* slab = reinterpret_cast<uint16_t*>(smem);                          // [2][128][WLDS]
+    uint16_t* otile = reinterpret_cast<uint16_t*>(smem);                         // [128][WLDO], after the K loop
+    uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)WBM * WLDO * 2); // [128]
+    uint32_t total = *a.esc_count;
+    total = total < a.esc_cap ? total : a.esc_cap;
+    const uint32_t row0 = a.row_begin + blockIdx.x * WBM; // first escalated row of this block
+    if (row0 >= total) return;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t col0 = blockIdx.y * WBN;
+    const uint32_t nb_total = (a.N + 31u) / 32u;
+    const uint32_t KS = (a.K + WSLAB - 1) / WSLAB * WRING; // k-steps, padded to whole slabs
+    const uint32_t n_slabs = KS / WRING;
+    const uint32_t nb0 = col0 / 32u + wave * WNI;
+
+    if (AMODE != A_BF16) {
+        if (tid < WBM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : 0u;
+        __syncthreads();
+    }
+    // two 16-byte chunks of the slab per thread: rows r, 8 k-values each
+    const uint32_t cr[2] = {tid / (WSLAB / 8), (tid + WWAVES * 64) / (WSLAB / 8)};
+    const uint32_t ck = (tid % (WSLAB / 8)) * 8u;
+    uint4 ra[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u], AMODE != A_BF16 ? s_flow[cr[u]] : 0u, ck);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) *reinterpret_cast<uint4*>(slab + cr[u] * WLDS + ck) = ra[u];
+
+    // accumulators start at the bias of their column
+    f32x16 acc[WMI][WNI];
+#pragma unroll
+    for (int j = 0; j < WNI; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t col = (nb0 + j) * 32u + 8u * g + 4u * (lane >> 5);
+            float b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) b[q] = col + q < a.N ? a.bias[col + q] : 0.f;
+#pragma unroll
+            for (int i = 0; i < WMI; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[i][j][4 * g + q] = b[q];
+        }
+    // weight operands: a column block past the end repeats the last one, its results are not stored
+    const bool wave_has_cols = nb0 < nb_total;
+    const uint4* wl[WNI];
+#pragma unroll
+    for (int j = 0; j < WNI; ++j) {
+        const uint32_t nb = nb0 + j < nb_total ? nb0 + j : nb_total - 1u;
+        wl[j] = ws + (size_t)nb * KS * 64u;
+    }
+    uint4 fb[WRING][WNI];
+#pragma unroll
+    for (int s = 0; s < WRING; ++s)
+#pragma unroll
+        for (int j = 0; j < WNI; ++j) fb[s][j] = wl[j][s * 64 + lane];
+    __syncthreads(); // slab 0 is in place
+
+    for (uint32_t sl = 0; sl < n_slabs; ++sl) {
+        const bool more = sl + 1 < n_slabs;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u],
+                                            AMODE != A_BF16 ? s_flow[cr[u]] : 0u, (sl + 1) * WSLAB + ck);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (wave_has_cols) {
+            const uint16_t* arow = slab + (sl & 1u) * (WBM * WLDS) + (lane & 31u) * WLDS + 8u * (lane >> 5);
+#pragma unroll
+            for (int s = 0; s < WRING; ++s) {
+                uint4 fa[WMI];
+#pragma unroll
+                for (int i = 0; i < WMI; ++i) fa[i] = *reinterpret_cast<const uint4*>(arow + i * 32 * WLDS + s * 16);
+#pragma unroll
+                for (int j = 0; j < WNI; ++j) {
+                    const bf16x8 b = as_bf16x8(fb[s][j]);
+#pragma unroll
+                    for (int i = 0; i < WMI; ++i)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, as_bf16x8(fa[i]), acc[i][j], 0, 0, 0);
+                }
+                // refill for the same step of the next slab (past the end: the next block or the padding)
+#pragma unroll
+                for (int j = 0; j < WNI; ++j) fb[s][j] = wl[j][((sl + 1) * WRING + s) * 64u + lane];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                *reinterpret_cast<uint4*>(slab + ((sl + 1) & 1u) * (WBM * WLDS) + cr[u] * WLDS + ck) = ra[u];
+        }
+        __syncthreads(); // the next slab is in place; nobody reads this one any more
+    }
+
+    // epilogue: relu, bfloat16, stage the tile, then whole rows to memory
+#pragma unroll
+    for (int j = 0; j < WNI; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t cl = wave * 64u + j * 32u + 8u * g + 4u * (lane >> 5); // column inside the tile
+#pragma unroll
+            for (int i = 0; i < WMI; ++i) {
+                const uint32_t row = i * 32u + (lane & 31u);
+                const float y0 = fmaxf(acc[i][j][4 * g + 0], 0.f), y1 = fmaxf(acc[i][j][4 * g + 1], 0.f);
+                const float y2 = fmaxf(acc[i][j][4 * g + 2], 0.f), y3 = fmaxf(acc[i][j][4 * g + 3], 0.f);
+                *reinterpret_cast<uint2*>(otile + row * WLDO + cl) = make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3));
+            }
+        }
+    __syncthreads();
+    // 64 chunks of 8 columns per row; columns in [N, ldh) are padding and were computed as zeros
+    for (uint32_t c = tid; c < WBM * (WBN / 8); c += WWAVES * 64u) {
+        const uint32_t r = c / (WBN / 8), k = (c % (WBN / 8)) * 8u;
+        if (row0 + r < total && col0 + k < a.ldh) {
+            const uint4 v = *reinterpret_cast<const uint4*>(otile + r * WLDO + k);
+            uint16_t* dst = a.h_out + (size_t)(blockIdx.x * WBM + r) * a.ldh + col0 + k;
+            if (col0 + k + 8u <= a.ldh && (a.ldh & 7u) == 0) {
+                *reinterpret_cast<uint4*>(dst) = v;
+            } else {
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                for (uint32_t q = 0; q < 8u && col0 + k + q < a.ldh; ++q) dst[q] = (uint16_t)(w[q >> 1] >> (16u * (q & 1u)));
+            }
+        }
+    }
+}
+
+template <int AMODE>
+int launch_wide(sf_ctx* ctx, const LayerArgs& a, const void* w_ordered, uint32_t rows_cap)
+{
+    SF_HIP(ctx, hipFuncSetAttribute((const void*)mlp_wide_layer<AMODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)kWideLds));
+    dim3 grid((rows_cap + WBM - 1) / WBM, (a.ldh + WBN - 1) / WBN);
+    mlp_wide_layer<AMODE><<<grid, WWAVES * 64, kWideLds, ctx->stream>>>(a, (const uint4*)w_ordered);
+    SF_LAUNCH_CHECK(ctx, "mlp_wide_layer");
+    return SF_OK;
+}
+
+} // namespace
+
+namespace sf {
+
+int wide_layer(sf_ctx* ctx, int amode, const sfmlp::LayerArgs& a, const void* w_ordered, uint32_t rows_cap)
+{
+    if (amode == A_BF16) return launch_wide<A_BF16>(ctx, a, w_ordered, rows_cap);
+    if (amode == A_FEAT) return launch_wide<A_FEAT>(ctx, a, w_ordered, rows_cap);
+    return launch_wide<A_RAW>(ctx, a, w_ordered, rows_cap);
+}
+
+} // namespace sf

@@ -21,9 +21,9 @@ class GpuRun:
         self.cfg, self.n = cfg, pk.n_flows
         dev = "cuda:0"
         n = self.n
-        h1, h2 = (mlp.dims[1], mlp.dims[2]) if mlp is not None else (0, 0)
+        n_in, h1, h2 = mlp.dims[:3] if mlp is not None else (0, 0, 0)
         if ws_bytes is None:
-            ws_bytes = sf.sf_workspace_bytes(max(n, 1), cfg.n_trees, cfg.tree_depth, h1, h2)
+            ws_bytes = sf.sf_workspace_bytes(max(n, 1), cfg.n_trees, cfg.tree_depth, n_in, h1, h2)
         self.ctx = sf.ServeFlow(ws_bytes)
         self.pk = sf.packets_to_device(pk, dev)
         self.forest = sf.forest_to_device(forest, dev) if forest is not None else None

@@ -74,9 +74,11 @@ def test_vmin_from_theta_exact(lib):
 
 
 def test_workspace_bytes_monotone(lib):
-    a = lib.sf_workspace_bytes(4096, 16, 8, 128, 128)
-    b = lib.sf_workspace_bytes(1 << 20, 100, 12, 512, 512)
-    c = lib.sf_workspace_bytes(1 << 20, 100, 12, 0, 0)
+    a = lib.sf_workspace_bytes(4096, 16, 8, 32, 128, 128)
+    b = lib.sf_workspace_bytes(1 << 20, 100, 12, 64, 512, 512)
+    c = lib.sf_workspace_bytes(1 << 20, 100, 12, 0, 0, 0)
+    d = lib.sf_workspace_bytes(1 << 20, 100, 12, 4800, 1024, 512)
+    assert d - lib.sf_workspace_bytes(1 << 20, 100, 12, 64, 1024, 512) >= (4800 - 64) * 1024 * 2   # ordered first-layer weights
     assert 0 < a < b and c < b and a % 256 == 0 and b % 256 == 0
     assert c >= 100 * 1365 * 16         # the packed forest alone: (4^6-1)/3 two-level records of 16 bytes per tree
 

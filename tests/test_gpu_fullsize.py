@@ -25,7 +25,7 @@ def _full(cfg_id, n, vmin, logit_sample):
     o_esc = oracle.route(o_top, o_pred, vmin)
 
     dev = "cuda:0"
-    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, mlp.dims[1], mlp.dims[2]))
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, *mlp.dims[:3]))
     d_pk, d_forest, d_mlp = sf.packets_to_device(pk, dev), sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
     feat = torch.empty((n, cfg.n_features), dtype=torch.float32, device=dev)
     pred = torch.empty(n, dtype=torch.int16, device=dev)

@@ -235,30 +235,31 @@ def test_whole_path_raw_bits():
 
 
 def test_slow_infer_row_chunks_and_cap():
-    """A workspace that holds only 256 rows forces several row chunks; a capacity below the count
-    leaves the flows beyond it with their fast label."""
+    """A workspace provisioned for 256 rows forces several row chunks in the layer-by-layer path
+    (hidden width 1024); a capacity below the count leaves the flows beyond it with their fast label
+    (checked on both the layer-by-layer and the fused path)."""
     import paper_2402_03694_amd as sf
-    cfg, pk, feat, forest, mlp = _small(2, 2000)
-    vmin = 16
-    want = oracle.classify(pk, cfg.depths, forest, vmin, mlp, n_threads=8)
-    E = want["esc_idx"].size
-    assert E > 900
-    small_ws = sf.sf_workspace_bytes(2000, cfg.n_trees, cfg.tree_depth, 0, 0) + 300 * (512 + 512) * 2 + 2048
-    run = _run(cfg, pk, forest, mlp, ws_bytes=small_ws)
-    run.featurize()
-    _, g_pred, _, _ = run.fast_infer()
-    esc, cnt = run.route(vmin)
-    logits, labels = run.slow_infer()
-    _check_slow(cfg, logits, labels, want["logits"], want["labels"], esc, g_pred, BF16_TOL, BF16_MARGIN)
-    cap = 700
-    run2 = _run(cfg, pk, forest, mlp, esc_cap=cap)
-    run2.featurize()
-    run2.fast_infer()
-    run2.route(vmin)
-    logits2, labels2 = run2.slow_infer()
-    assert np.abs(logits2[:cap] - want["logits"][:cap]).max() <= BF16_TOL
-    beyond = esc[cap:]
-    assert np.array_equal(labels2[beyond], g_pred[beyond])
+    for cfg_id, vmin in ((4, 19), (2, 16)):
+        cfg, pk, feat, forest, mlp = _small(cfg_id, 2000)
+        want = oracle.classify(pk, cfg.depths, forest, vmin, mlp, n_threads=8)
+        E = want["esc_idx"].size
+        assert E > 700
+        small_ws = sf.sf_workspace_bytes(256, cfg.n_trees, cfg.tree_depth, *mlp.dims[:3])
+        run = _run(cfg, pk, forest, mlp, ws_bytes=small_ws)
+        run.featurize()
+        _, g_pred, _, _ = run.fast_infer()
+        esc, cnt = run.route(vmin)
+        logits, labels = run.slow_infer()
+        _check_slow(cfg, logits, labels, want["logits"], want["labels"], esc, g_pred, BF16_TOL, BF16_MARGIN)
+        cap = 600
+        run2 = _run(cfg, pk, forest, mlp, esc_cap=cap)
+        run2.featurize()
+        run2.fast_infer()
+        run2.route(vmin)
+        logits2, labels2 = run2.slow_infer()
+        assert np.abs(logits2[:cap] - want["logits"][:cap]).max() <= BF16_TOL
+        beyond = esc[cap:]
+        assert np.array_equal(labels2[beyond], g_pred[beyond])
 
 
 def test_error_paths_return_codes():
