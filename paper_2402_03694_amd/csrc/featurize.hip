@@ -75,7 +75,8 @@ __device__ __forceinline__ void order_stats(const float (&x)[KMAX], uint64_t gm,
     uint32_t key[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const uint32_t k = IS_TIME ? order_key(x[i]) : (__float_as_uint(x[i]) ^ 0x80000000u); // sizes are >= 0
+        // packet sizes are >= 0, so their bit pattern already orders like the value
+        const uint32_t k = IS_TIME ? order_key(x[i]) : __float_as_uint(x[i]);
         key[i] = bit_of(gm, i) ? k : 0xFFFFFFFFu;
     }
     sort_network<N>(key);
@@ -83,9 +84,9 @@ __device__ __forceinline__ void order_stats(const float (&x)[KMAX], uint64_t gm,
     for (int i = 0; i < N; ++i) col[i * kWave] = key[i];
     const int last = cg > 0 ? cg - 1 : 0;
     const uint32_t klo = col[(last >> 1) * kWave], khi = col[(cg >> 1) * kWave], kmx = col[last * kWave];
-    mn = from_key(key[0]);
-    mx = from_key(kmx);
-    const float lo = from_key(klo), hi = from_key(khi);
+    mn = IS_TIME ? from_key(key[0]) : __uint_as_float(key[0]);
+    mx = IS_TIME ? from_key(kmx) : __uint_as_float(kmx);
+    const float lo = IS_TIME ? from_key(klo) : __uint_as_float(klo), hi = IS_TIME ? from_key(khi) : __uint_as_float(khi);
     const float two = lo + hi;
     med = (cg & 1) ? hi : two * 0.5f;
 }
@@ -132,9 +133,10 @@ __device__ __forceinline__ void window_stats(const float (&s)[KMAX], const float
         qT0 = qT0 + (d0 ? gb2 : 0.f);
         qT1 = qT1 + (d1 ? gb2 : 0.f);
     }
-    // per group: assemble the ten statistics (the group index is a run-time loop so that the
-    // sorting network is emitted twice, not six times)
-#pragma unroll 1
+    // per group: assemble the ten statistics (for the larger networks the group index is a run-time
+    // loop so that the sorting network is emitted twice, not six times)
+    constexpr int kGroupUnroll = N <= 16 ? 3 : 1;
+#pragma unroll kGroupUnroll
     for (int g = 0; g < 3; ++g) {
         const uint64_t gm = g == 0 ? m0 : (g == 1 ? m1 : valid);
         const int cg = g == 0 ? c0 : (g == 1 ? c1 : m);
