@@ -41,6 +41,8 @@ def _load():
         _lib.oracle_vmin_from_theta.restype = ctypes.c_uint32
         _lib.oracle_vmin_from_theta.argtypes = [ctypes.c_float, ctypes.c_uint32]
         _lib.oracle_route.restype = ctypes.c_uint32
+        _lib.oracle_route_ratio.restype = ctypes.c_uint32
+        _lib.oracle_tree_infer.restype = ctypes.c_int
         for name in ("oracle_featurize", "oracle_fast_infer", "oracle_slow_infer",
                      "oracle_universal_thresholds", "oracle_max_window"):
             getattr(_lib, name).restype = ctypes.c_int
@@ -121,6 +123,34 @@ def route(top_votes, pred, vmin) -> np.ndarray:
     return esc[:cnt].copy()
 
 
+def tree_infer(feat, tree, want_leaves: bool = False, n_threads: int = 1):
+    """tree: any object with depth, n_classes, n_features, node_feat, node_thr, leaf_count.
+    Returns (pred, top_count, leaf_total, leaf_idx or None)."""
+    lib = _load()
+    feat = _c(feat, np.float32)
+    n, ld = feat.shape
+    nf, nt, lc = _c(tree.node_feat, np.uint16), _c(tree.node_thr, np.float32), _c(tree.leaf_count, np.uint16)
+    assert nf.shape == ((1 << tree.depth) - 1,) and lc.shape == (1 << tree.depth, tree.n_classes)
+    pred, top, tot = (np.zeros(n, np.uint16) for _ in range(3))
+    leaves = np.zeros(n, np.uint16) if want_leaves else None
+    rc = lib.oracle_tree_infer(ctypes.c_uint32(n), _p(feat), ctypes.c_uint32(ld), ctypes.c_uint32(tree.depth),
+                               ctypes.c_uint32(tree.n_classes), ctypes.c_uint32(tree.n_features), _p(nf),
+                               _p(nt), _p(lc), _p(pred), _p(top), _p(tot), _p(leaves), ctypes.c_int(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_tree_infer: invalid arguments")
+    return pred, top, tot, leaves
+
+
+def route_ratio(top_count, leaf_total, theta) -> np.ndarray:
+    lib = _load()
+    top_count, leaf_total = _c(top_count, np.uint16), _c(leaf_total, np.uint16)
+    n = top_count.shape[0]
+    esc = np.zeros(max(n, 1), np.uint32)
+    cnt = lib.oracle_route_ratio(ctypes.c_uint32(n), _p(top_count), _p(leaf_total),
+                                 ctypes.c_float(np.float32(theta)), _p(esc))
+    return esc[:cnt].copy()
+
+
 def universal_thresholds(scores, quantiles) -> np.ndarray:
     lib = _load()
     s, q = _c(scores, np.float64), _c(quantiles, np.float64)
@@ -164,6 +194,22 @@ def slow_infer(esc_idx, mlp, n_flows: int, feat=None, flow_off=None, pkt_hdr=Non
     if rc != 0:
         raise ValueError("oracle_slow_infer: invalid arguments")
     return logits, labels
+
+
+def classify3(pk, depths, tree, theta0, forest, vmin, mlp, n_threads: int = 1):
+    """The three-tier cascade of Section 3.1: the tree on every flow, the forest on the flows
+    the tree is unsure of, the MLP on the flows the forest is unsure of; a later tier's label
+    replaces the earlier one (Section 4.4).  Lists are in flow numbering, ascending."""
+    feat, _ = featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, depths, n_threads=n_threads)
+    pred0, top0, tot0, leaf0 = tree_infer(feat, tree, want_leaves=True, n_threads=n_threads)
+    esc1 = route_ratio(top0, tot0, theta0)
+    votes, pred1, top1, _ = fast_infer(feat[esc1], forest, n_threads=n_threads)   # rows follow esc1
+    esc2 = esc1[route(top1, pred1, vmin)]
+    labels = pred0.copy()
+    labels[esc1] = pred1
+    logits, labels = slow_infer(esc2, mlp, feat.shape[0], feat=feat, labels=labels, n_threads=n_threads)
+    return dict(feat=feat, pred0=pred0, top0=top0, total0=tot0, leaf0=leaf0, esc1=esc1, votes1=votes,
+                pred1=pred1, top1=top1, esc2=esc2, logits=logits, labels=labels)
 
 
 def classify(pk, depths, forest, vmin, mlp, raw_pkts=0, raw_bits=0, n_threads: int = 1):

@@ -21,7 +21,9 @@
  * numpy's mean/std/min/max/median, a brute-force bit loop, hand-traced and
  * recursively walked trees, the multinomial closed form for the top-vote
  * histogram, set/ordering invariants of the gate, numpy's float64 matmul and
- * the identity / one-hot / dead-ReLU special cases of the MLP.
+ * the identity / one-hot / dead-ReLU special cases of the MLP; for the tree tier
+ * a decision tree fitted by scikit-learn (predict, predict_proba), a hand-traced
+ * tree and exact rational arithmetic for the ratio gate.
  * Accuracy of the classifier itself (F1 etc.) is parity unpinned: it needs the
  * paper's datasets and trained models.
  */
@@ -233,6 +235,90 @@ uint32_t oracle_route(uint32_t n_flows, const uint16_t *top_votes, const uint16_
         uint16_t th = n_vmin == 1 ? vmin[0] : vmin[pred[i]];
         if (top_votes[i] < th) esc_idx[e++] = i;
     }
+    return e;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The tier in front of the fast model (Section 3.1: the "fastest" model, a single
+ * decision tree, sees every flow first; Section 4.1: its leaves keep enough
+ * training samples, at least 15, for the leaf's class distribution to serve as the
+ * uncertainty estimate).
+ *
+ * Reading used where the paper is silent: a perfect binary tree in heap order with
+ * the same split rule as the forest (x[f] <= thr goes left); leaf_count[leaf][c]
+ * = number of training samples of class c that reached the leaf;
+ *   P(y|x) = leaf_count[leaf][y] / leaf_total,  leaf_total = sum_c leaf_count[leaf][c];
+ *   pred = arg-max, lowest class on ties;  top_count = leaf_count[leaf][pred];
+ *   LC(x) = 1 - top_count / leaf_total  (Section 3.2).
+ * A leaf total must fit 16 bits. */
+int oracle_tree_infer(uint32_t n_flows, const float *feat, uint32_t feat_ld, uint32_t depth,
+                      uint32_t n_classes, uint32_t n_features, const uint16_t *node_feat,
+                      const float *node_thr, const uint16_t *leaf_count /* [2^depth][n_classes] */,
+                      uint16_t *pred, uint16_t *top_count, uint16_t *leaf_total,
+                      uint16_t *leaf_idx /* [n_flows] or NULL */, int n_threads)
+{
+    if (depth < 1 || depth > 15 || n_classes < 1 || n_features < 1 || n_features > feat_ld) return -1;
+    const uint32_t n_int = (1u << depth) - 1u, n_leaf = 1u << depth;
+    for (uint32_t q = 0; q < n_int; ++q)
+        if (node_feat[q] >= n_features) return -1;
+    for (uint32_t l = 0; l < n_leaf; ++l) {
+        uint64_t tot = 0;
+        for (uint32_t c = 0; c < n_classes; ++c) tot += leaf_count[(size_t)l * n_classes + c];
+        if (tot > 65535u) return -1;
+    }
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+    for (int64_t i = 0; i < (int64_t)n_flows; ++i) {
+        const float *x = feat + (size_t)i * feat_ld;
+        uint32_t k = 0;
+        for (uint32_t s = 0; s < depth; ++s)
+            k = 2 * k + 1 + (x[node_feat[k]] <= node_thr[k] ? 0u : 1u);
+        const uint32_t leaf = k - n_int;
+        const uint16_t *cnt = leaf_count + (size_t)leaf * n_classes;
+        uint32_t best = 0, tot = 0;
+        for (uint32_t c = 0; c < n_classes; ++c) {
+            tot += cnt[c];
+            if (cnt[c] > cnt[best]) best = c;
+        }
+        pred[i] = (uint16_t)best;
+        top_count[i] = cnt[best];
+        leaf_total[i] = (uint16_t)tot;
+        if (leaf_idx) leaf_idx[i] = (uint16_t)leaf;
+    }
+    return 0;
+}
+
+/* top/total < theta without rounding anything: theta = m * 2^e with an integer m
+ * (a binary32 value has 24 significant bits), so the test is top * 2^-e < m * total
+ * in integers.  A leaf without samples has no distribution: P(y|x) is read as 0 for
+ * every y, LC = 1, and the flow escalates for any positive theta. */
+static int ratio_below(uint32_t top, uint32_t total, float theta)
+{
+    if (!(theta > 0.0f)) return 0;
+    if (total == 0) return 1;
+    int e;
+    double fr = frexp((double)theta, &e);          /* theta = fr * 2^e, 0.5 <= fr < 1 */
+    unsigned __int128 m = (unsigned __int128)(uint64_t)ldexp(fr, 24);
+    e -= 24;                                       /* theta = m * 2^e, m < 2^24       */
+    unsigned __int128 lhs = top, rhs = m * total;  /* rhs < 2^40                      */
+    if (e >= 0) {
+        if (e > 64) return 1;                      /* theta*total >= 2^64 > top       */
+        rhs <<= e;
+    } else {
+        if (-e > 64) return top == 0;              /* theta*total < 1                 */
+        lhs <<= -e;
+    }
+    return lhs < rhs;
+}
+
+/* Gate of the tree tier: escalate iff max_y P(y|x) < theta, i.e. LC(x) > 1 - theta
+ * (Section 3.2).  Ascending index list; returns its length. */
+uint32_t oracle_route_ratio(uint32_t n_flows, const uint16_t *top_count, const uint16_t *leaf_total,
+                            float theta, uint32_t *esc_idx)
+{
+    uint32_t e = 0;
+    for (uint32_t i = 0; i < n_flows; ++i)
+        if (ratio_below(top_count[i], leaf_total[i], theta)) esc_idx[e++] = i;
     return e;
 }
 

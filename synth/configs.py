@@ -1,4 +1,4 @@
-"""The five synthetic workload configurations.
+"""The synthetic workload configurations: five two-tier ones and a three-tier cascade.
 
 Each mirrors one regime the paper discusses: a handful of first packets as
 context (Section 3.1), a tree model as the fast tier and a heavier model as the
@@ -35,6 +35,10 @@ class WorkloadConfig:
     data_seed: int = 1000
     model_seed: int = 2000
     calib_flows: int = 4096                  # flows whose features feed thresholds / standardisation
+    # three-tier cascade (Section 3.1): a single decision tree in front of the forest; 0 = none
+    tree0_depth: int = 0
+    tree0_features: int = 0                  # the tree and the forest split on the first this-many columns
+    theta0: Optional[float] = None           # the tree escalates a flow iff max_y P(y|x) < theta0
 
     @property
     def n_features(self) -> int:
@@ -72,6 +76,14 @@ CONFIGS = {
         n_trees=500, tree_depth=10, n_classes=32, target_fracs=(0.05, 0.25, 0.50),
         mlp_dims=(128, 2048, 2048, 32), mlp_dtype="bf16",
         data_seed=1005, model_seed=2005),
+    # the cascade the paper evaluates (decision tree, then a boosted/bagged ensemble, then the
+    # slow model; Section 5.2): config 2's shape with a depth-10 tree on the first window
+    6: WorkloadConfig(
+        name="cfg6_three_tier", n_flows=1 << 20, pkts_per_flow=16, depths=(8, 16),
+        n_trees=100, tree_depth=12, n_classes=10, vmin=14,
+        mlp_dims=(64, 512, 512, 10), mlp_dtype="bf16",
+        tree0_depth=10, tree0_features=32, theta0=0.6,
+        data_seed=1006, model_seed=2006),
 }
 
 

@@ -24,6 +24,16 @@ class Forest:
 
 
 @dataclass
+class Tree:
+    depth: int
+    n_classes: int
+    n_features: int
+    node_feat: np.ndarray    # uint16 [2^d - 1], heap order
+    node_thr: np.ndarray     # float32 [2^d - 1]
+    leaf_count: np.ndarray   # uint16 [2^d, C]: training samples of each class at the leaf
+
+
+@dataclass
 class Mlp:
     dims: tuple              # (n_in, n_h1, n_h2, n_classes)
     dtype: str               # "f32" | "bf16" (weights are bf16-representable float32 when "bf16")
@@ -62,11 +72,35 @@ def make_forest(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int
     T, d, C = cfg.n_trees, cfg.tree_depth, cfg.n_classes
     F = feat_sample.shape[1]
     n_int = (1 << d) - 1
-    node_feat = rng.integers(0, F, size=(T, n_int), dtype=np.uint16)
+    node_feat = rng.integers(0, cfg.tree0_features or F, size=(T, n_int), dtype=np.uint16)
     pick = rng.integers(0, feat_sample.shape[0], size=(T, n_int))
     node_thr = np.ascontiguousarray(feat_sample[pick, node_feat.astype(np.int64)], dtype=np.float32)
     leaf_label = rng.integers(0, C, size=(T, 1 << d), dtype=np.uint8)
     return Forest(T, d, C, F, node_feat, node_thr, leaf_label)
+
+
+def make_tree(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int] = None) -> Tree:
+    """The single decision tree of the first tier.  Splits as in make_forest, on the first
+    cfg.tree0_features columns.  Leaf class counts: the leaf holds 15 + Poisson(45) samples
+    (the paper keeps at least 15 per leaf), a uniformly drawn majority class with share
+    p ~ U(0.15, 1) and the rest spread evenly, drawn as one multinomial."""
+    seed = cfg.model_seed if seed is None else seed
+    rng = np.random.Generator(np.random.PCG64(seed * 1000 + 3))
+    d, C = cfg.tree0_depth, cfg.n_classes
+    F = cfg.tree0_features or feat_sample.shape[1]
+    n_int, n_leaf = (1 << d) - 1, 1 << d
+    node_feat = rng.integers(0, F, size=n_int, dtype=np.uint16)
+    pick = rng.integers(0, feat_sample.shape[0], size=n_int)
+    node_thr = np.ascontiguousarray(feat_sample[pick, node_feat.astype(np.int64)], dtype=np.float32)
+    total = 15 + rng.poisson(45.0, size=n_leaf)
+    major = rng.integers(0, C, size=n_leaf)
+    share = rng.uniform(0.15, 1.0, size=n_leaf)
+    leaf_count = np.zeros((n_leaf, C), dtype=np.uint16)
+    for l in range(n_leaf):
+        p = np.full(C, (1.0 - share[l]) / max(C - 1, 1))
+        p[major[l]] = share[l] if C > 1 else 1.0
+        leaf_count[l] = rng.multinomial(int(total[l]), p / p.sum())
+    return Tree(d, C, feat_sample.shape[1], node_feat, node_thr, leaf_count)
 
 
 def _xavier(rng, fan_out, fan_in):
