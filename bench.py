@@ -83,12 +83,112 @@ def cpu_baseline(cfg, sample_flows, vmin):
                       % (sample_flows, dt, 100.0 * out["esc_idx"].size / sample_flows)}
 
 
+def three_tier(args, cfg):
+    """--config 6: the cascade of Section 3.1 (tree on every flow, forest on the tree's uncertain flows,
+    MLP on the forest's uncertain flows); a step is all seven calls over one device-resident batch."""
+    import torch
+    import synth
+    import paper_2402_03694_amd as sf
+    dev = "cuda:0"
+    n = args.flows or cfg.n_flows
+    pk = synth.make_packets(cfg, n_flows=n)
+    F, C = cfg.n_features, cfg.n_classes
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, *cfg.mlp_dims[:3]))
+    d_pk = sf.packets_to_device(pk, dev)
+    feat = torch.empty((n, F), dtype=torch.float32, device=dev)
+    i16 = lambda m: torch.empty(m, dtype=torch.int16, device=dev)
+    i32 = lambda m: torch.zeros(m, dtype=torch.int32, device=dev)
+    top0, tot0, pred1, top1, labels = i16(n), i16(n), i16(n), i16(n), i16(n)
+    esc1, cnt1, esc2, cnt2 = i32(n), i32(1), i32(n), i32(1)
+    ctx.sf_featurize(d_pk, cfg.depths, feat)
+    torch.cuda.synchronize()
+    calib = feat[: cfg.calib_flows].cpu().numpy()
+    tree, forest, mlp = synth.make_tree(cfg, calib), synth.make_forest(cfg, calib), synth.make_mlp(cfg, calib)
+    d_tree, d_forest, d_mlp = sf.tree_to_device(tree, dev), sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
+    ctx.sf_validate_tree(d_tree)
+    ctx.sf_validate_forest(d_forest)
+    names = ["sf_featurize", "sf_fastest_infer", "sf_route_ratio", "sf_fast_infer_subset", "sf_route_subset",
+             "sf_slow_infer"]
+
+    def step(ev=None):
+        rec = (lambda i: ev[i].record()) if ev else (lambda i: None)
+        rec(0)
+        ctx.sf_featurize(d_pk, cfg.depths, feat)
+        rec(1)
+        ctx.sf_fastest_infer(feat, d_tree, labels, top0, tot0)      # the tree's label is the flow's label ...
+        rec(2)
+        ctx.sf_route_ratio(top0, tot0, cfg.theta0, esc1, cnt1)
+        rec(3)
+        ctx.sf_fast_infer_subset(feat, esc1, cnt1, d_forest, pred1, top1, labels=labels)   # ... until the forest's
+        rec(4)
+        ctx.sf_route_subset(top1, pred1, esc1, cnt1, cfg.vmin, esc2, cnt2)
+        rec(5)
+        ctx.sf_slow_infer(d_mlp, esc2, cnt2, labels, feat=feat)     # ... or the MLP's replaces it (Section 4.4)
+        rec(6)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n1 = int(cnt1.cpu().numpy().view(np.uint32)[0])
+    n2 = int(cnt2.cpu().numpy().view(np.uint32)[0])
+    call_ms = np.array([[ev[i].elapsed_time(ev[i + 1]) for i in range(6)] for ev in events])
+    avg = call_ms.mean(axis=0)
+    k1b, _, _ = algorithmic_bytes(cfg, n, pk.n_pkts, 0.0)
+    used = cfg.tree0_features or F
+    bytes_ = [k1b, (4 * used + 6) * n, 4 * n + 4 * n1, (4 * used + 4 + 4) * n1, (2 + 4) * n1 + 4 * n2, None]
+    kernels = {}
+    for i, nm in enumerate(names[:5]):
+        a = bytes_[i] / (avg[i] * 1e-3) / 1e9
+        kernels[nm] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
+                       "traffic": None, "ms": float(avg[i]), "bytes": bytes_[i]}
+    visits = float(n1) * cfg.n_trees * cfg.tree_depth
+    kernels["sf_fast_infer_subset"].update(node_visits=visits, visits_per_s=visits / (avg[3] * 1e-3))
+    tf = mlp_flops(cfg, n2) / (avg[5] * 1e-3) / 1e12
+    kernels["sf_slow_infer"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "ms": float(avg[5]),
+                                "flops": mlp_flops(cfg, n2)}
+    dominant = names[int(np.argmax(avg))]
+    roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    roof["kernel"] = dominant
+    out = {
+        "metric": "flows/sec end-to-end (tree + gated forest + gated slow)",
+        "value": n * args.steps / (t1 - t0), "unit": "flows/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": (t1 - t0) * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 features, integer counts and votes, %s MLP" % cfg.mlp_dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d flows, %d packets, F=%d, tree depth %d theta0=%.2f, T=%d depth %d C=%d vmin=%d, "
+                               "MLP %s %s" % (cfg.name, n, pk.n_pkts, F, cfg.tree0_depth, cfg.theta0, cfg.n_trees,
+                                              cfg.tree_depth, C, cfg.vmin, cfg.mlp_dtype, "x".join(map(str, cfg.mlp_dims))),
+                   "to_forest_fraction": n1 / n, "to_mlp_fraction": n2 / n},
+        "roofline": roof, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.default_threads()
+        sample = args.cpu_sample or min(n, 1 << 20)
+        spk = synth.make_packets(cfg, n_flows=sample)
+        t0 = time.perf_counter()
+        o = oracle.classify3(spk, cfg.depths, tree, cfg.theta0, forest, cfg.vmin, mlp, n_threads=threads)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample / dt, "unit": "flows/s", "cores": threads, "kind": "oracle",
+                               "sample": "first %d flows, all three tiers, %.1f s wall, %.1f%% to the forest, %.1f%% to "
+                                         "the MLP" % (sample, dt, 100.0 * o["esc1"].size / sample,
+                                                      100.0 * o["esc2"].size / sample)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the 1M-flow headline workload)")
+    ap.add_argument("--config", type=int, default=2, help="workload 1..6 (2 = the 1M-flow headline workload, 6 = the three-tier cascade)")
     ap.add_argument("--flows", type=int, default=0, help="override the flow count (for quick runs)")
     ap.add_argument("--target", type=float, default=-1.0, help="override the escalated-fraction target")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -111,6 +211,8 @@ def main():
     dev = "cuda:0"
 
     cfg = synth.get_config(args.config)
+    if cfg.tree0_depth:
+        return three_tier(args, cfg)
     n = args.flows or cfg.n_flows
     pk = synth.make_packets(cfg, n_flows=n)
     n_pkts = pk.n_pkts

@@ -177,6 +177,55 @@ int sf_universal_thresholds(const uint32_t* host_hist, uint32_t n_trees, const d
 uint32_t sf_vmin_for_target(const uint32_t* host_hist, uint32_t n_trees, double target_fraction,
                             double* reached_fraction);
 
+/* ---- three tiers: a single decision tree in front of the fast model ----------------------
+ * Section 3.1: a "fastest" model (a decision tree) sees every flow first; only the flows it
+ * is unsure of go on to the fast model, and only those the fast model is unsure of reach the
+ * slow one.  Section 4.1: the tree's leaves keep the class counts of their training samples
+ * (at least 15 per leaf), which make the leaf a distribution: P(y|x) = leaf_count[leaf][y] /
+ * leaf_total, leaf_total = sum over y.  Section 3.2: LC(x) = 1 - max_y P(y|x).
+ *
+ * The tree is perfect, in heap order, with the split rule of sf_forest.  pred = the class
+ * with the largest count at the leaf (lowest index on ties), top_count = that count. */
+typedef struct {
+    uint32_t depth, n_classes, n_features; /* depth 1..SF_MAX_TREE_DEPTH                      */
+    const uint16_t* node_feat;  /* [2^depth - 1], values < n_features                          */
+    const float* node_thr;      /* [2^depth - 1]                                               */
+    const uint16_t* leaf_count; /* [2^depth][n_classes]; a leaf's counts sum to at most 65535  */
+} sf_tree;
+
+/* feat: [n_flows][feat_ld].  pred, top_count, leaf_total: [n_flows]; leaf_idx: optional
+ * [n_flows] (for parity checks).  Uses workspace (16 bytes per leaf). */
+int sf_fastest_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
+                     const sf_tree* tree, uint16_t* pred, uint16_t* top_count, uint16_t* leaf_total,
+                     uint16_t* leaf_idx);
+
+/* Waits, then checks node_feat < n_features, leaf totals <= 65535 and thresholds not NaN. */
+int sf_validate_tree(sf_ctx* ctx, const sf_tree* tree);
+
+/* The gate of the tree tier: flow i escalates iff top_count[i] / leaf_total[i] < theta, i.e.
+ * LC above 1 - theta, evaluated without rounding (theta's binary32 value times a 16-bit total
+ * is exact in binary64).  A leaf without samples (leaf_total 0) escalates for any theta > 0.
+ * Outputs as sf_route. */
+int sf_route_ratio(sf_ctx* ctx, const uint16_t* top_count, const uint16_t* leaf_total, uint32_t n_flows,
+                   float theta, uint32_t* esc_idx, uint32_t* esc_count);
+
+/* The fast model on the flows of a list only.  idx / idx_count: as written by sf_route or
+ * sf_route_ratio (device); at most idx_cap entries are read; entries >= n_flows are clamped.
+ * Row j of the outputs belongs to flow idx[j]: pred, top_votes: [idx_cap]; votes: optional
+ * [idx_cap][n_classes].  labels: optional [n_flows]; labels[idx[j]] = pred[j] (the fast
+ * label replaces the tree's).  Rows from *idx_count on are not written. */
+int sf_fast_infer_subset(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
+                         const uint32_t* idx, const uint32_t* idx_count, uint32_t idx_cap,
+                         const sf_forest* forest, uint16_t* votes, uint16_t* pred, uint16_t* top_votes,
+                         uint16_t* labels);
+
+/* sf_route over the rows of such a list: row j escalates iff top_votes[j] < vmin (per-class:
+ * host_vmin[pred[j]]); esc_idx receives the FLOW numbers idx[j] of the escalated rows, which
+ * are ascending because idx is; *esc_count their number.  Capacity of esc_idx: idx_cap. */
+int sf_route_subset(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, const uint32_t* idx,
+                    const uint32_t* idx_count, uint32_t idx_cap, const uint16_t* host_vmin, uint32_t n_vmin,
+                    uint32_t* esc_idx, uint32_t* esc_count);
+
 /* ---- step 5: slow model on the escalated flows only ------------------------------------
  * Sections 3.1 and 4.4: only flows the fast model is unsure of reach the slow model, and
  * its answer replaces the fast one.  The slow model is a 3-layer ReLU MLP.

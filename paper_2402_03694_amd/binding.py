@@ -21,7 +21,8 @@ SF_MAX_WINDOWS = 4
 EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf_featurize",
            "sf_validate_packets", "sf_fast_infer", "sf_validate_forest", "sf_route",
            "sf_vmin_from_theta", "sf_slow_infer", "sf_score_histogram", "sf_universal_thresholds",
-           "sf_vmin_for_target")
+           "sf_vmin_for_target", "sf_fastest_infer", "sf_validate_tree", "sf_route_ratio",
+           "sf_fast_infer_subset", "sf_route_subset")
 
 
 class SfPackets(ctypes.Structure):
@@ -41,6 +42,11 @@ class SfForest(ctypes.Structure):
                 ("n_classes", ctypes.c_uint32), ("n_features", ctypes.c_uint32),
                 ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p),
                 ("leaf_label", ctypes.c_void_p)]
+
+
+class SfTree(ctypes.Structure):
+    _fields_ = [("depth", ctypes.c_uint32), ("n_classes", ctypes.c_uint32), ("n_features", ctypes.c_uint32),
+                ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p), ("leaf_count", ctypes.c_void_p)]
 
 
 class SfMlp(ctypes.Structure):
@@ -86,6 +92,16 @@ def load_library() -> ctypes.CDLL:
     lib.sf_slow_infer.restype = ctypes.c_int
     lib.sf_slow_infer.argtypes = [vp, vp, u32, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), vp, vp,
                                   u32, u32, ctypes.POINTER(SfMlp), vp, vp, vp]
+    lib.sf_fastest_infer.restype = ctypes.c_int
+    lib.sf_fastest_infer.argtypes = [vp, vp, u32, u32, ctypes.POINTER(SfTree), vp, vp, vp, vp]
+    lib.sf_validate_tree.restype = ctypes.c_int
+    lib.sf_validate_tree.argtypes = [vp, ctypes.POINTER(SfTree)]
+    lib.sf_route_ratio.restype = ctypes.c_int
+    lib.sf_route_ratio.argtypes = [vp, vp, vp, u32, ctypes.c_float, vp, vp]
+    lib.sf_fast_infer_subset.restype = ctypes.c_int
+    lib.sf_fast_infer_subset.argtypes = [vp, vp, u32, u32, vp, vp, u32, ctypes.POINTER(SfForest), vp, vp, vp, vp]
+    lib.sf_route_subset.restype = ctypes.c_int
+    lib.sf_route_subset.argtypes = [vp, vp, vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
     lib.sf_score_histogram.restype = ctypes.c_int
     lib.sf_score_histogram.argtypes = [vp, vp, u32, u32, ctypes.POINTER(ctypes.c_uint32)]
     lib.sf_universal_thresholds.restype = ctypes.c_int
@@ -180,6 +196,20 @@ class DeviceForest:
         s.node_feat = _ptr(self.node_feat, torch.int16).value
         s.node_thr = _ptr(self.node_thr, torch.float32).value
         s.leaf_label = _ptr(self.leaf_label, torch.uint8).value
+        return s
+
+
+class DeviceTree:
+    def __init__(self, depth, n_classes, n_features, node_feat, node_thr, leaf_count):
+        self.depth, self.n_classes, self.n_features = depth, n_classes, n_features
+        self.node_feat, self.node_thr, self.leaf_count = node_feat, node_thr, leaf_count
+
+    def c_struct(self) -> SfTree:
+        s = SfTree()
+        s.depth, s.n_classes, s.n_features = self.depth, self.n_classes, self.n_features
+        s.node_feat = _ptr(self.node_feat, torch.int16).value
+        s.node_thr = _ptr(self.node_thr, torch.float32).value
+        s.leaf_count = _ptr(self.leaf_count, torch.int16).value
         return s
 
 
@@ -282,6 +312,48 @@ class ServeFlow:
         n = int(top_votes.shape[0]) if n_flows is None else n_flows
         self._check(self._lib.sf_route(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr, len(vm),
                                        _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    # ---- the tier in front of the fast model and the list forms of steps 2-4 ----------------
+    def sf_fastest_infer(self, feat: torch.Tensor, tree: DeviceTree, pred: torch.Tensor, top_count: torch.Tensor,
+                         leaf_total: torch.Tensor, leaf_idx: Optional[torch.Tensor] = None,
+                         n_flows: Optional[int] = None):
+        t = tree.c_struct()
+        n = int(feat.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_fastest_infer(self._h, _ptr(feat, torch.float32), int(feat.shape[1]), n,
+                                               ctypes.byref(t), _ptr(pred, torch.int16), _ptr(top_count, torch.int16),
+                                               _ptr(leaf_total, torch.int16), _ptr(leaf_idx, torch.int16)))
+
+    def sf_validate_tree(self, tree: DeviceTree):
+        t = tree.c_struct()
+        self._check(self._lib.sf_validate_tree(self._h, ctypes.byref(t)))
+
+    def sf_route_ratio(self, top_count: torch.Tensor, leaf_total: torch.Tensor, theta: float, esc_idx: torch.Tensor,
+                       esc_count: torch.Tensor, n_flows: Optional[int] = None):
+        n = int(top_count.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_route_ratio(self._h, _ptr(top_count, torch.int16), _ptr(leaf_total, torch.int16), n,
+                                             ctypes.c_float(theta), _ptr(esc_idx, torch.int32),
+                                             _ptr(esc_count, torch.int32)))
+
+    def sf_fast_infer_subset(self, feat: torch.Tensor, idx: torch.Tensor, idx_count: torch.Tensor,
+                             forest: DeviceForest, pred: torch.Tensor, top_votes: torch.Tensor,
+                             votes: Optional[torch.Tensor] = None, labels: Optional[torch.Tensor] = None,
+                             idx_cap: Optional[int] = None):
+        f = forest.c_struct()
+        cap = int(pred.shape[0]) if idx_cap is None else int(idx_cap)
+        self._check(self._lib.sf_fast_infer_subset(
+            self._h, _ptr(feat, torch.float32), int(feat.shape[1]), int(feat.shape[0]), _ptr(idx, torch.int32),
+            _ptr(idx_count, torch.int32), cap, ctypes.byref(f), _ptr(votes, torch.int16), _ptr(pred, torch.int16),
+            _ptr(top_votes, torch.int16), _ptr(labels, torch.int16)))
+
+    def sf_route_subset(self, top_votes: torch.Tensor, pred: Optional[torch.Tensor], idx: torch.Tensor,
+                        idx_count: torch.Tensor, vmin, esc_idx: torch.Tensor, esc_count: torch.Tensor,
+                        idx_cap: Optional[int] = None):
+        vm = [int(vmin)] if isinstance(vmin, int) else [int(v) for v in vmin]
+        arr = (ctypes.c_uint16 * len(vm))(*vm)
+        cap = int(top_votes.shape[0]) if idx_cap is None else int(idx_cap)
+        self._check(self._lib.sf_route_subset(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16),
+                                              _ptr(idx, torch.int32), _ptr(idx_count, torch.int32), cap, arr, len(vm),
+                                              _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
 
     def sf_score_histogram(self, top_votes: torch.Tensor, n_trees: int, n_flows: Optional[int] = None):
         n = int(top_votes.shape[0]) if n_flows is None else n_flows

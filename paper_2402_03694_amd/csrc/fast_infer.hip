@@ -60,7 +60,11 @@ __global__ __launch_bounds__(256) void pack_forest(uint32_t n_trees, uint32_t de
 struct FastArgs {
     const float* feat;
     uint32_t ld;
-    uint32_t n_flows;
+    uint32_t n_flows;          // rows to classify (the capacity of the list when idx is given)
+    const uint32_t* idx;       // subset form: row j is flow idx[j]; NULL = row j is flow j
+    const uint32_t* idx_count; // subset form: device-side length of idx
+    uint32_t n_rows;           // subset form: rows of feat (list entries are clamped below it)
+    uint16_t* labels;          // subset form, optional: labels[idx[j]] = pred of row j
     uint32_t n_trees, depth, n_classes, n_features;
     uint32_t top_pairs; // pair-levels of every tree staged in shared memory
     uint32_t vote_bits; // width of one packed vote counter: 8 (n_trees <= 255) or 16
@@ -99,8 +103,18 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     const uint32_t grp = lane / FPW;                       // which share of the trees this lane walks
     const uint32_t slot = wave * FPW + (lane % FPW);       // flow slot in the block's tile
     const uint32_t i = blockIdx.x * FPB + slot;
-    const bool live = i < a.n_flows;
-    const uint32_t row = live ? i : a.n_flows - 1; // idle lanes walk a valid row, write nothing
+    uint32_t n = a.n_flows;
+    if (a.idx_count) {
+        const uint32_t c = *a.idx_count;
+        n = c < n ? c : n;
+        if (blockIdx.x * FPB >= n) return; // the list ends before this block's tile (whole block leaves)
+    }
+    const bool live = i < n;
+    uint32_t row = live ? i : n - 1; // idle lanes walk a valid row, write nothing
+    if (a.idx) {
+        row = a.idx[row];
+        row = row < a.n_rows ? row : a.n_rows - 1u; // a bad list entry must not leave the matrix
+    }
     {
         // the S lanes of a flow each copy 1/S of its row into the flow's column
         const float* x = a.feat + (size_t)row * a.ld;
@@ -234,6 +248,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     }
     a.pred[i] = (uint16_t)best;
     a.top[i] = (uint16_t)bestv;
+    if (a.labels) a.labels[row] = (uint16_t)best;
 }
 
 template <int BS, int S>
@@ -264,11 +279,13 @@ size_t forest_pack_bytes(uint32_t n_trees, uint32_t depth)
 }
 } // namespace sf
 
-extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
-                             const sf_forest* forest, uint16_t* votes, uint16_t* pred, uint16_t* top_votes,
-                             uint16_t* leaf_idx)
+namespace {
+
+// both entry points: n_flows rows (all flows, or the capacity of the list idx)
+int run_forest(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows, const uint32_t* idx,
+               const uint32_t* idx_count, uint32_t n_rows, const sf_forest* forest, uint16_t* votes, uint16_t* pred,
+               uint16_t* top_votes, uint16_t* leaf_idx, uint16_t* labels)
 {
-    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_fast_infer: ctx is NULL");
     if (!forest) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: forest is NULL");
     if (forest->depth < 1 || forest->depth > SF_MAX_TREE_DEPTH)
         return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: depth %u outside 1..%d", forest->depth, SF_MAX_TREE_DEPTH);
@@ -304,6 +321,10 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     a.feat = feat;
     a.ld = feat_ld;
     a.n_flows = n_flows;
+    a.idx = idx;
+    a.idx_count = idx_count;
+    a.n_rows = n_rows;
+    a.labels = labels;
     a.n_trees = forest->n_trees;
     a.depth = forest->depth;
     a.n_classes = forest->n_classes;
@@ -349,4 +370,27 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     if (lds > 160 * 1024) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_fast_infer: %zu bytes of shared memory needed", lds);
     if (split == 2) return launch_votes<256, 2>(ctx, a, lds);
     return launch_votes<256, 1>(ctx, a, lds);
+}
+
+} // namespace
+
+extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
+                             const sf_forest* forest, uint16_t* votes, uint16_t* pred, uint16_t* top_votes,
+                             uint16_t* leaf_idx)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_fast_infer: ctx is NULL");
+    return run_forest(ctx, feat, feat_ld, n_flows, nullptr, nullptr, n_flows, forest, votes, pred, top_votes, leaf_idx,
+                      nullptr);
+}
+
+extern "C" int sf_fast_infer_subset(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
+                                    const uint32_t* idx, const uint32_t* idx_count, uint32_t idx_cap,
+                                    const sf_forest* forest, uint16_t* votes, uint16_t* pred, uint16_t* top_votes,
+                                    uint16_t* labels)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_fast_infer_subset: ctx is NULL");
+    if (idx_cap && n_flows == 0) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer_subset: a list over zero flows");
+    if (idx_cap && (!idx || !idx_count)) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer_subset: idx or idx_count is NULL");
+    return run_forest(ctx, feat, feat_ld, idx_cap, idx, idx_count, n_flows, forest, votes, pred, top_votes, nullptr,
+                      labels);
 }

@@ -1,5 +1,8 @@
 // Step 4: the gate of Section 3.2 of the paper in integer form, and the compaction of the
-// uncertain flows into an ascending index list.
+// uncertain flows into an ascending index list.  Three forms of the gate share the kernels:
+// votes against a threshold (universal or per predicted class), a leaf's class share against
+// theta (the single-tree tier), and either of them over the rows of an earlier list (the
+// second gate of a three-tier cascade, Section 3.1), which writes flow numbers, not rows.
 //
 // Two launches, no spinning between blocks: the first counts the escalated flows of each
 // block's contiguous chunk; the second adds up the counts of the blocks before it, then
@@ -19,6 +22,10 @@ constexpr uint32_t kMaxBlocks = 4096;
 struct RouteArgs {
     const uint16_t* top;
     const uint16_t* pred;
+    const uint16_t* total;     // ratio gate: per-row denominators (NULL = vote gate)
+    float theta;               // ratio gate: escalate iff top / total < theta
+    const uint32_t* src_idx;   // rows are the entries of this list (NULL = rows are flows)
+    const uint32_t* src_count; // device-side length of that list (n is then its capacity)
     uint32_t n;
     uint32_t chunk; // flows per block, a multiple of kTile
     uint32_t n_vmin;
@@ -28,12 +35,35 @@ struct RouteArgs {
     uint32_t* esc_count;
 };
 
-// 8-bit mask of the lane's flows [base, base+8) that escalate
-__device__ __forceinline__ uint32_t gate_mask(const RouteArgs& a, uint32_t base)
+// rows the gate runs over: the whole array, or as many as the earlier list holds
+__device__ __forceinline__ uint32_t live_rows(const RouteArgs& a)
+{
+    if (!a.src_count) return a.n;
+    const uint32_t c = *a.src_count;
+    return c < a.n ? c : a.n;
+}
+
+// top / total < theta without rounding: binary32 theta times a 16-bit total is exact in binary64.
+// A leaf without samples has no distribution; it escalates for any positive theta.
+__device__ __forceinline__ bool ratio_below(uint32_t top, uint32_t total, float theta)
+{
+    if (total == 0) return theta > 0.f;
+    return (double)top < (double)theta * (double)total;
+}
+
+// 8-bit mask of the lane's rows [base, base+8) that escalate; n = live_rows(a)
+__device__ __forceinline__ uint32_t gate_mask(const RouteArgs& a, uint32_t n, uint32_t base)
 {
     uint32_t m = 0;
-    if (base >= a.n) return 0;
-    if (base + kPerLane <= a.n && a.n_vmin == 1) {
+    if (base >= n) return 0;
+    if (a.total) {
+        for (int k = 0; k < kPerLane; ++k) {
+            const uint32_t i = base + k;
+            if (i < n) m |= (ratio_below(a.top[i], a.total[i], a.theta) ? 1u : 0u) << k;
+        }
+        return m;
+    }
+    if (base + kPerLane <= n && a.n_vmin == 1) {
         // base is a multiple of 8: the 16-byte load is aligned whenever top is
         uint16_t v[kPerLane];
         if ((reinterpret_cast<uintptr_t>(a.top) & 15u) == 0) {
@@ -55,7 +85,7 @@ __device__ __forceinline__ uint32_t gate_mask(const RouteArgs& a, uint32_t base)
     }
     for (int k = 0; k < kPerLane; ++k) {
         const uint32_t i = base + k;
-        if (i < a.n) {
+        if (i < n) {
             uint16_t th = a.vmin[0];
             if (a.n_vmin > 1) {
                 uint32_t p = a.pred[i];
@@ -102,8 +132,9 @@ __global__ __launch_bounds__(kBlock) void route_count(RouteArgs a)
 {
     __shared__ uint32_t sm[kBlock / 64];
     const uint32_t begin = blockIdx.x * a.chunk;
+    const uint32_t n = live_rows(a);
     uint32_t c = 0;
-    for (uint32_t t = 0; t < a.chunk; t += kTile) c += __popc(gate_mask(a, begin + t + threadIdx.x * kPerLane));
+    for (uint32_t t = 0; t < a.chunk; t += kTile) c += __popc(gate_mask(a, n, begin + t + threadIdx.x * kPerLane));
     const uint32_t inc = wave_inclusive_scan(c);
     if ((threadIdx.x & 63) == 63) sm[threadIdx.x >> 6] = inc;
     __syncthreads();
@@ -123,14 +154,15 @@ __global__ __launch_bounds__(kBlock) void route_scatter(RouteArgs a)
     uint32_t run;
     block_exclusive_scan(part, sm, run);
     const uint32_t begin = blockIdx.x * a.chunk;
+    const uint32_t n = live_rows(a);
     for (uint32_t t = 0; t < a.chunk; t += kTile) {
         const uint32_t base = begin + t + threadIdx.x * kPerLane;
-        const uint32_t m = gate_mask(a, base);
+        const uint32_t m = gate_mask(a, n, base);
         uint32_t tile_total;
         uint32_t pos = run + block_exclusive_scan(__popc(m), sm, tile_total);
 #pragma unroll
         for (int k = 0; k < kPerLane; ++k)
-            if (m & (1u << k)) a.esc_idx[pos++] = base + k;
+            if (m & (1u << k)) a.esc_idx[pos++] = a.src_idx ? a.src_idx[base + k] : base + k;
         run += tile_total;
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *a.esc_count = run;
@@ -172,40 +204,20 @@ __global__ __launch_bounds__(256) void hist_scores(const uint16_t* __restrict__ 
     }
 }
 
-} // namespace
-
-extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
-                        const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count)
+// shared launch of the two kernels; a.top, a.pred, a.total, a.theta, a.src_*, a.n, a.n_vmin and
+// a.vmin are filled by the caller
+int launch_route(sf_ctx* ctx, const char* who, RouteArgs& a, uint32_t* esc_idx, uint32_t* esc_count)
 {
-    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route: ctx is NULL");
-    if (!host_vmin || n_vmin < 1 || n_vmin > SF_MAX_CLASSES)
-        return sf::fail(ctx, SF_EINVAL, "sf_route: host_vmin missing or n_vmin %u outside 1..%d", n_vmin,
-                        SF_MAX_CLASSES);
-    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route: esc_count is NULL");
-    if (n_flows == 0) {
-        route_zero<<<1, 1, 0, ctx->stream>>>(esc_count);
-        SF_LAUNCH_CHECK(ctx, "route_zero");
-        return SF_OK;
-    }
-    if (n_flows > (1u << 31)) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route: more than 2^31 flows per call");
-    if (!top_votes || !esc_idx) return sf::fail(ctx, SF_EINVAL, "sf_route: top_votes or esc_idx is NULL");
-    if (n_vmin > 1 && !pred) return sf::fail(ctx, SF_EINVAL, "sf_route: per-class thresholds need pred");
-
     sf::Carve ws(ctx);
     // workspace contents do not outlive a call: every entry point carves from the start
-    uint32_t* counts = (uint32_t*)ws.take(sf::route_scratch_bytes(n_flows));
-    if (!counts) return sf::fail(ctx, SF_ENOMEM, "sf_route: workspace too small for %zu bytes of block counts",
-                                 sf::route_scratch_bytes(n_flows));
-    RouteArgs a;
-    a.top = top_votes;
-    a.pred = pred;
-    a.n = n_flows;
-    uint64_t tiles = ((uint64_t)n_flows + kTile - 1) / kTile;
+    uint32_t* counts = (uint32_t*)ws.take(sf::route_scratch_bytes(a.n));
+    if (!counts)
+        return sf::fail(ctx, SF_ENOMEM, "%s: workspace too small for %zu bytes of block counts", who,
+                        sf::route_scratch_bytes(a.n));
+    uint64_t tiles = ((uint64_t)a.n + kTile - 1) / kTile;
     uint64_t tiles_per_block = (tiles + kMaxBlocks - 1) / kMaxBlocks;
     a.chunk = (uint32_t)(tiles_per_block * kTile);
     const uint32_t grid = (uint32_t)((tiles + tiles_per_block - 1) / tiles_per_block);
-    a.n_vmin = n_vmin;
-    for (uint32_t c = 0; c < SF_MAX_CLASSES; ++c) a.vmin[c] = host_vmin[c < n_vmin ? c : n_vmin - 1];
     a.counts = counts;
     a.esc_idx = esc_idx;
     a.esc_count = esc_count;
@@ -214,6 +226,87 @@ extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* 
     route_scatter<<<grid, kBlock, 0, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "route_scatter");
     return SF_OK;
+}
+
+int zero_count(sf_ctx* ctx, uint32_t* esc_count)
+{
+    route_zero<<<1, 1, 0, ctx->stream>>>(esc_count);
+    SF_LAUNCH_CHECK(ctx, "route_zero");
+    return SF_OK;
+}
+
+int fill_vmin(sf_ctx* ctx, const char* who, RouteArgs& a, const uint16_t* host_vmin, uint32_t n_vmin)
+{
+    if (!host_vmin || n_vmin < 1 || n_vmin > SF_MAX_CLASSES)
+        return sf::fail(ctx, SF_EINVAL, "%s: host_vmin missing or n_vmin %u outside 1..%d", who, n_vmin, SF_MAX_CLASSES);
+    a.n_vmin = n_vmin;
+    for (uint32_t c = 0; c < SF_MAX_CLASSES; ++c) a.vmin[c] = host_vmin[c < n_vmin ? c : n_vmin - 1];
+    return SF_OK;
+}
+
+} // namespace
+
+extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
+                        const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route: ctx is NULL");
+    RouteArgs a = {};
+    {
+        const int rc = fill_vmin(ctx, "sf_route", a, host_vmin, n_vmin);
+        if (rc != SF_OK) return rc;
+    }
+    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route: esc_count is NULL");
+    if (n_flows == 0) return zero_count(ctx, esc_count);
+    if (n_flows > (1u << 31)) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route: more than 2^31 flows per call");
+    if (!top_votes || !esc_idx) return sf::fail(ctx, SF_EINVAL, "sf_route: top_votes or esc_idx is NULL");
+    if (n_vmin > 1 && !pred) return sf::fail(ctx, SF_EINVAL, "sf_route: per-class thresholds need pred");
+    a.top = top_votes;
+    a.pred = pred;
+    a.n = n_flows;
+    return launch_route(ctx, "sf_route", a, esc_idx, esc_count);
+}
+
+extern "C" int sf_route_ratio(sf_ctx* ctx, const uint16_t* top_count, const uint16_t* leaf_total, uint32_t n_flows,
+                              float theta, uint32_t* esc_idx, uint32_t* esc_count)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route_ratio: ctx is NULL");
+    if (theta != theta) return sf::fail(ctx, SF_EINVAL, "sf_route_ratio: theta is NaN");
+    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route_ratio: esc_count is NULL");
+    if (n_flows == 0) return zero_count(ctx, esc_count);
+    if (n_flows > (1u << 31)) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route_ratio: more than 2^31 flows per call");
+    if (!top_count || !leaf_total || !esc_idx)
+        return sf::fail(ctx, SF_EINVAL, "sf_route_ratio: top_count, leaf_total or esc_idx is NULL");
+    RouteArgs a = {};
+    a.top = top_count;
+    a.total = leaf_total;
+    a.theta = theta;
+    a.n = n_flows;
+    a.n_vmin = 1;
+    return launch_route(ctx, "sf_route_ratio", a, esc_idx, esc_count);
+}
+
+extern "C" int sf_route_subset(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, const uint32_t* idx,
+                               const uint32_t* idx_count, uint32_t idx_cap, const uint16_t* host_vmin,
+                               uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route_subset: ctx is NULL");
+    RouteArgs a = {};
+    {
+        const int rc = fill_vmin(ctx, "sf_route_subset", a, host_vmin, n_vmin);
+        if (rc != SF_OK) return rc;
+    }
+    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route_subset: esc_count is NULL");
+    if (idx_cap == 0) return zero_count(ctx, esc_count);
+    if (idx_cap > (1u << 31)) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route_subset: more than 2^31 rows per call");
+    if (!top_votes || !esc_idx || !idx || !idx_count)
+        return sf::fail(ctx, SF_EINVAL, "sf_route_subset: top_votes, idx, idx_count or esc_idx is NULL");
+    if (n_vmin > 1 && !pred) return sf::fail(ctx, SF_EINVAL, "sf_route_subset: per-class thresholds need pred");
+    a.top = top_votes;
+    a.pred = pred;
+    a.src_idx = idx;
+    a.src_count = idx_count;
+    a.n = idx_cap;
+    return launch_route(ctx, "sf_route_subset", a, esc_idx, esc_count);
 }
 
 // ---- calibration entry points ------------------------------------------------------------------

@@ -2,7 +2,7 @@
 import numpy as np
 import torch
 
-from .binding import SF_BF16, SF_F32, DeviceForest, DeviceMlp, DevicePackets
+from .binding import SF_BF16, SF_F32, DeviceForest, DeviceMlp, DevicePackets, DeviceTree
 
 
 def _dev(a: np.ndarray, device) -> torch.Tensor:
@@ -25,6 +25,11 @@ def packets_to_device(pk, device="cuda:0", with_hdr: bool = True) -> DevicePacke
 def forest_to_device(f, device="cuda:0") -> DeviceForest:
     return DeviceForest(f.n_trees, f.depth, f.n_classes, f.n_features, _dev(f.node_feat, device),
                         _dev(f.node_thr, device), _dev(f.leaf_label, device))
+
+
+def tree_to_device(t, device="cuda:0") -> DeviceTree:
+    return DeviceTree(t.depth, t.n_classes, t.n_features, _dev(t.node_feat, device), _dev(t.node_thr, device),
+                      _dev(t.leaf_count, device))
 
 
 def mlp_to_device(m, device="cuda:0") -> DeviceMlp:

@@ -72,7 +72,8 @@ def make_forest(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int
     T, d, C = cfg.n_trees, cfg.tree_depth, cfg.n_classes
     F = feat_sample.shape[1]
     n_int = (1 << d) - 1
-    node_feat = rng.integers(0, cfg.tree0_features or F, size=(T, n_int), dtype=np.uint16)
+    F = cfg.tree0_features or F           # a cascade's forest splits on the same columns as its tree
+    node_feat = rng.integers(0, F, size=(T, n_int), dtype=np.uint16)
     pick = rng.integers(0, feat_sample.shape[0], size=(T, n_int))
     node_thr = np.ascontiguousarray(feat_sample[pick, node_feat.astype(np.int64)], dtype=np.float32)
     leaf_label = rng.integers(0, C, size=(T, 1 << d), dtype=np.uint8)
@@ -100,7 +101,7 @@ def make_tree(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int] 
         p = np.full(C, (1.0 - share[l]) / max(C - 1, 1))
         p[major[l]] = share[l] if C > 1 else 1.0
         leaf_count[l] = rng.multinomial(int(total[l]), p / p.sum())
-    return Tree(d, C, feat_sample.shape[1], node_feat, node_thr, leaf_count)
+    return Tree(d, C, F, node_feat, node_thr, leaf_count)
 
 
 def _xavier(rng, fan_out, fan_in):
