@@ -43,6 +43,8 @@ def _load():
         _lib.oracle_route.restype = ctypes.c_uint32
         _lib.oracle_route_ratio.restype = ctypes.c_uint32
         _lib.oracle_tree_infer.restype = ctypes.c_int
+        _lib.oracle_gbdt_infer.restype = ctypes.c_int
+        _lib.oracle_route_score.restype = ctypes.c_uint32
         for name in ("oracle_featurize", "oracle_fast_infer", "oracle_slow_infer",
                      "oracle_universal_thresholds", "oracle_max_window"):
             getattr(_lib, name).restype = ctypes.c_int
@@ -148,6 +150,37 @@ def route_ratio(top_count, leaf_total, theta) -> np.ndarray:
     esc = np.zeros(max(n, 1), np.uint32)
     cnt = lib.oracle_route_ratio(ctypes.c_uint32(n), _p(top_count), _p(leaf_total),
                                  ctypes.c_float(np.float32(theta)), _p(esc))
+    return esc[:cnt].copy()
+
+
+def gbdt_infer(feat, model, want_margins: bool = True, n_threads: int = 1):
+    """model: any object with n_trees, depth, n_classes, n_features, node_feat, node_thr, leaf_value, base.
+    Returns (margins float32 [n, C] or None, pred, lc float64, entropy float64)."""
+    lib = _load()
+    feat = _c(feat, np.float32)
+    n, ld = feat.shape
+    T, C = model.n_trees, model.n_classes
+    nf, nt, lv = _c(model.node_feat, np.uint16), _c(model.node_thr, np.float32), _c(model.leaf_value, np.float32)
+    assert nf.shape == (T, (1 << model.depth) - 1) and lv.shape == (T, 1 << model.depth)
+    base = None if model.base is None else _c(model.base, np.float32)
+    margins = np.zeros((n, C), np.float32) if want_margins else None
+    pred = np.zeros(n, np.uint16)
+    lc, ent = np.zeros(n, np.float64), np.zeros(n, np.float64)
+    rc = lib.oracle_gbdt_infer(ctypes.c_uint32(n), _p(feat), ctypes.c_uint32(ld), ctypes.c_uint32(T),
+                               ctypes.c_uint32(model.depth), ctypes.c_uint32(C), ctypes.c_uint32(model.n_features),
+                               _p(nf), _p(nt), _p(lv), _p(base), _p(margins), _p(pred), _p(lc), _p(ent),
+                               ctypes.c_int(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_gbdt_infer: invalid arguments")
+    return margins, pred, lc, ent
+
+
+def route_score(score, threshold) -> np.ndarray:
+    lib = _load()
+    score = _c(score, np.float32)
+    n = score.shape[0]
+    esc = np.zeros(max(n, 1), np.uint32)
+    cnt = lib.oracle_route_score(ctypes.c_uint32(n), _p(score), ctypes.c_float(np.float32(threshold)), _p(esc))
     return esc[:cnt].copy()
 
 

@@ -23,7 +23,10 @@
  * histogram, set/ordering invariants of the gate, numpy's float64 matmul and
  * the identity / one-hot / dead-ReLU special cases of the MLP; for the tree tier
  * a decision tree fitted by scikit-learn (predict, predict_proba), a hand-traced
- * tree and exact rational arithmetic for the ratio gate.
+ * tree and exact rational arithmetic for the ratio gate; for the boosted form a
+ * gradient-boosting classifier fitted by scikit-learn (decision_function,
+ * predict_proba), scipy's softmax and entropy, and a sum whose result depends on
+ * the order of the additions.
  * Accuracy of the classifier itself (F1 etc.) is parity unpinned: it needs the
  * paper's datasets and trained models.
  */
@@ -319,6 +322,77 @@ uint32_t oracle_route_ratio(uint32_t n_flows, const uint16_t *top_count, const u
     uint32_t e = 0;
     for (uint32_t i = 0; i < n_flows; ++i)
         if (ratio_below(top_count[i], leaf_total[i], theta)) esc_idx[e++] = i;
+    return e;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Boosted-tree form of the fast model (Section 4.1 names gradient-boosted trees,
+ * the fast and slow models of the evaluated cascade in Section 5.2 are of that
+ * kind) with the two uncertainty scores of Section 3.2:
+ *   LC(x) = 1 - max_y P(y|x)          H(x) = - sum_i P(y_i|x) log P(y_i|x).
+ *
+ * Reading used where the paper is silent (the usual multiclass boosting layout):
+ * tree t belongs to class t mod C and boosting round t div C; its leaves hold a
+ * binary32 margin; the class margin is
+ *   m[c] = base[c] + leaf(c) + leaf(C + c) + leaf(2C + c) + ...
+ * added in that order, every addition rounded to binary32 (so that a second
+ * implementation can reproduce it bit for bit);  P(.|x) = softmax(m), evaluated
+ * in binary64 from the binary32 margins with the maximum subtracted first;
+ * pred = arg-max of m, lowest class on ties; log is natural; 0 log 0 = 0.
+ * Trees are perfect, heap order, x[f] <= thr goes left, as everywhere here. */
+int oracle_gbdt_infer(uint32_t n_flows, const float *feat, uint32_t feat_ld, uint32_t n_trees,
+                      uint32_t depth, uint32_t n_classes, uint32_t n_features,
+                      const uint16_t *node_feat, const float *node_thr,
+                      const float *leaf_value /* [n_trees][2^depth] */, const float *base /* [C] */,
+                      float *margin /* [n][C] or NULL */, uint16_t *pred, double *lc, double *entropy,
+                      int n_threads)
+{
+    if (depth < 1 || depth > 15 || n_classes < 1 || n_trees < 1 || n_features > feat_ld) return -1;
+    const uint32_t n_int = (1u << depth) - 1u, n_leaf = 1u << depth;
+    for (size_t q = 0; q < (size_t)n_trees * n_int; ++q)
+        if (node_feat[q] >= n_features) return -1;
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+    for (int64_t i = 0; i < (int64_t)n_flows; ++i) {
+        const float *x = feat + (size_t)i * feat_ld;
+        float *m = (float *)malloc(sizeof(float) * n_classes);
+        for (uint32_t c = 0; c < n_classes; ++c) m[c] = base ? base[c] : 0.0f;
+        for (uint32_t t = 0; t < n_trees; ++t) {
+            const uint16_t *nf = node_feat + (size_t)t * n_int;
+            const float *nt = node_thr + (size_t)t * n_int;
+            uint32_t k = 0;
+            for (uint32_t s = 0; s < depth; ++s)
+                k = 2 * k + 1 + (x[nf[k]] <= nt[k] ? 0u : 1u);
+            float v = leaf_value[(size_t)t * n_leaf + (k - n_int)];
+            m[t % n_classes] = m[t % n_classes] + v;
+        }
+        uint32_t best = 0;
+        for (uint32_t c = 1; c < n_classes; ++c)
+            if (m[c] > m[best]) best = c;
+        double z = 0.0;
+        for (uint32_t c = 0; c < n_classes; ++c) z += exp((double)m[c] - (double)m[best]);
+        double h = 0.0;
+        for (uint32_t c = 0; c < n_classes; ++c) {
+            double p = exp((double)m[c] - (double)m[best]) / z;
+            if (p > 0.0) h -= p * log(p);
+        }
+        pred[i] = (uint16_t)best;
+        lc[i] = 1.0 - 1.0 / z; /* the largest probability is exp(0) / z */
+        entropy[i] = h;
+        if (margin)
+            for (uint32_t c = 0; c < n_classes; ++c) margin[(size_t)i * n_classes + c] = m[c];
+        free(m);
+    }
+    return 0;
+}
+
+/* Gate on a real-valued uncertainty score (Section 3.2): a flow is assigned to the
+ * slower model iff its score exceeds the threshold.  Ascending list; returns its length. */
+uint32_t oracle_route_score(uint32_t n_flows, const float *score, float threshold, uint32_t *esc_idx)
+{
+    uint32_t e = 0;
+    for (uint32_t i = 0; i < n_flows; ++i)
+        if (score[i] > threshold) esc_idx[e++] = i;
     return e;
 }
 

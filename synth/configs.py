@@ -1,4 +1,4 @@
-"""The synthetic workload configurations: five two-tier ones and a three-tier cascade.
+"""The synthetic workload configurations: five two-tier ones, a three-tier cascade and a boosted-tree one.
 
 Each mirrors one regime the paper discusses: a handful of first packets as
 context (Section 3.1), a tree model as the fast tier and a heavier model as the
@@ -39,6 +39,9 @@ class WorkloadConfig:
     tree0_depth: int = 0
     tree0_features: int = 0                  # the tree and the forest split on the first this-many columns
     theta0: Optional[float] = None           # the tree escalates a flow iff max_y P(y|x) < theta0
+    # boosted-tree form of the fast model (Section 4.1): leaves hold margins, softmax gives P(y|x)
+    fast_kind: str = "votes"                 # "votes" (hard-voting forest) | "gbdt"
+    score: str = "lc"                        # uncertainty score of the gbdt gate: "lc" | "entropy" (Section 3.2)
 
     @property
     def n_features(self) -> int:
@@ -84,6 +87,13 @@ CONFIGS = {
         mlp_dims=(64, 512, 512, 10), mlp_dtype="bf16",
         tree0_depth=10, tree0_features=32, theta0=0.6,
         data_seed=1006, model_seed=2006),
+    # the fast model as gradient-boosted trees (20 rounds x 10 classes, 256 leaves each), gated by
+    # the entropy of its softmax; threshold from Algorithm 1's quantile rule at the target portion
+    7: WorkloadConfig(
+        name="cfg7_gbdt_entropy", n_flows=1 << 20, pkts_per_flow=16, depths=(8, 16),
+        n_trees=200, tree_depth=8, n_classes=10, target_fracs=(0.25,),
+        mlp_dims=(64, 512, 512, 10), mlp_dtype="bf16", fast_kind="gbdt", score="entropy",
+        data_seed=1007, model_seed=2007),
 }
 
 

@@ -34,6 +34,18 @@ class Tree:
 
 
 @dataclass
+class Gbdt:
+    n_trees: int             # rounds * n_classes; tree t belongs to class t % n_classes
+    depth: int
+    n_classes: int
+    n_features: int
+    node_feat: np.ndarray    # uint16 [T, 2^d - 1], heap order
+    node_thr: np.ndarray     # float32 [T, 2^d - 1]
+    leaf_value: np.ndarray   # float32 [T, 2^d]: the margin a leaf adds to its tree's class
+    base: np.ndarray         # float32 [C]: initial margins
+
+
+@dataclass
 class Mlp:
     dims: tuple              # (n_in, n_h1, n_h2, n_classes)
     dtype: str               # "f32" | "bf16" (weights are bf16-representable float32 when "bf16")
@@ -102,6 +114,23 @@ def make_tree(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int] 
         p[major[l]] = share[l] if C > 1 else 1.0
         leaf_count[l] = rng.multinomial(int(total[l]), p / p.sum())
     return Tree(d, C, F, node_feat, node_thr, leaf_count)
+
+
+def make_gbdt(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int] = None) -> Gbdt:
+    """Boosted-tree fast model: splits as in make_forest; leaf margins N(0, 0.5^2) rounded to
+    binary32 (ten rounds then give class margins of spread ~1.6, a softmax that is neither flat
+    nor saturated); initial margins U(-0.5, 0.5)."""
+    seed = cfg.model_seed if seed is None else seed
+    rng = np.random.Generator(np.random.PCG64(seed * 1000 + 4))
+    T, d, C = cfg.n_trees, cfg.tree_depth, cfg.n_classes
+    F = feat_sample.shape[1]
+    n_int = (1 << d) - 1
+    node_feat = rng.integers(0, F, size=(T, n_int), dtype=np.uint16)
+    pick = rng.integers(0, feat_sample.shape[0], size=(T, n_int))
+    node_thr = np.ascontiguousarray(feat_sample[pick, node_feat.astype(np.int64)], dtype=np.float32)
+    leaf_value = rng.normal(0.0, 0.5, size=(T, 1 << d)).astype(np.float32)
+    base = rng.uniform(-0.5, 0.5, size=C).astype(np.float32)
+    return Gbdt(T, d, C, F, node_feat, node_thr, leaf_value, base)
 
 
 def _xavier(rng, fan_out, fan_in):
