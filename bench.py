@@ -65,18 +65,28 @@ def mlp_flops(cfg, n_rows):
 
 
 def cpu_baseline(cfg, sample_flows, vmin):
-    """The oracle as it stands, all four steps, on a bounded sample of the same workload."""
+    """The oracle as it stands, all four steps, on a bounded sample of the same workload
+    (vmin: the vote threshold, or the score threshold of the boosted form)."""
     import oracle
     import synth
     threads = oracle.default_threads()
     pk = synth.make_packets(cfg, n_flows=sample_flows)
     calib, _ = oracle.featurize(pk.flow_off[: cfg.calib_flows + 1], pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths,
                                 n_threads=threads)
-    forest = synth.make_forest(cfg, calib)
     mlp = synth.make_mlp(cfg, None if cfg.raw_pkts else calib)
-    t0 = time.perf_counter()
-    out = oracle.classify(pk, cfg.depths, forest, vmin, mlp, raw_pkts=cfg.raw_pkts, raw_bits=cfg.raw_bits,
-                          n_threads=threads)
+    if cfg.fast_kind == "gbdt":
+        model = synth.make_gbdt(cfg, calib)
+        t0 = time.perf_counter()
+        feat, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=threads)
+        _, pred, lc, ent = oracle.gbdt_infer(feat, model, want_margins=False, n_threads=threads)
+        esc = oracle.route_score((ent if cfg.score == "entropy" else lc).astype(np.float32), vmin)
+        oracle.slow_infer(esc, mlp, sample_flows, feat=feat, labels=pred.copy(), n_threads=threads)
+        out = {"esc_idx": esc}
+    else:
+        forest = synth.make_forest(cfg, calib)
+        t0 = time.perf_counter()
+        out = oracle.classify(pk, cfg.depths, forest, vmin, mlp, raw_pkts=cfg.raw_pkts, raw_bits=cfg.raw_bits,
+                              n_threads=threads)
     dt = time.perf_counter() - t0
     return {"value": sample_flows / dt, "unit": "flows/s", "cores": threads, "kind": "oracle",
             "sample": "first %d flows of the workload, all four steps, %.1f s wall, %.1f%% escalated"
@@ -231,18 +241,35 @@ def main():
     ctx.sf_featurize(d_pk, cfg.depths, feat)
     torch.cuda.synchronize()
     calib = feat[: cfg.calib_flows].cpu().numpy()
-    forest = synth.make_forest(cfg, calib)
+    gbdt = cfg.fast_kind == "gbdt"
     mlp = synth.make_mlp(cfg, None if cfg.raw_pkts else calib)
-    d_forest, d_mlp = sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
+    d_mlp = sf.mlp_to_device(mlp, dev)
     ctx.sf_validate_packets(d_pk)
-    ctx.sf_validate_forest(d_forest)
+    if gbdt:
+        d_model = sf.gbdt_to_device(synth.make_gbdt(cfg, calib), dev)
+        kind = sf.SF_SCORE_ENTROPY if cfg.score == "entropy" else sf.SF_SCORE_LC
+        score = torch.empty(n, dtype=torch.float32, device=dev)
+    else:
+        forest = synth.make_forest(cfg, calib)
+        d_forest = sf.forest_to_device(forest, dev)
+        ctx.sf_validate_forest(d_forest)
 
     # gate threshold: explicit, from theta, or the target-portion rule on this run's own scores
     # (target-portion rule of Section 3.2: the library histograms the integer score on the device and
     # picks the threshold whose escalated fraction is nearest the target; outside the timed region)
-    ctx.sf_fast_infer(feat, d_forest, pred, top)
-    hist = ctx.sf_score_histogram(top, cfg.n_trees)
-    if args.target >= 0:
+    if gbdt:
+        # boosted form: Algorithm 1's quantile rule on the real-valued score, on the device
+        ctx.sf_gbdt_infer(feat, d_model, kind, pred, score)
+        target = args.target if args.target >= 0 else cfg.target_fracs[len(cfg.target_fracs) // 2]
+        vmin = ctx.sf_score_quantiles(score, [1.0 - target])[0]
+        frac = target
+        hist = None
+    else:
+        ctx.sf_fast_infer(feat, d_forest, pred, top)
+        hist = ctx.sf_score_histogram(top, cfg.n_trees)
+    if gbdt:
+        pass
+    elif args.target >= 0:
         vmin, _ = sf.sf_vmin_for_target(hist, cfg.n_trees, args.target)
     elif cfg.vmin is not None:
         vmin = cfg.vmin
@@ -250,7 +277,8 @@ def main():
         vmin = sf.sf_vmin_from_theta(cfg.theta, cfg.n_trees)
     else:
         vmin, _ = sf.sf_vmin_for_target(hist, cfg.n_trees, cfg.target_fracs[len(cfg.target_fracs) // 2])
-    frac = sum(hist[:vmin]) / float(n)
+    if not gbdt:
+        frac = sum(hist[:vmin]) / float(n)
     esc_cap = n
 
     def step(ev=None):
@@ -259,10 +287,16 @@ def main():
         ctx.sf_featurize(d_pk, cfg.depths, feat)
         if ev:
             ev[1].record()
-        ctx.sf_fast_infer(feat, d_forest, pred, top)
+        if gbdt:
+            ctx.sf_gbdt_infer(feat, d_model, kind, pred, score)
+        else:
+            ctx.sf_fast_infer(feat, d_forest, pred, top)
         if ev:
             ev[2].record()
-        ctx.sf_route(top, pred, vmin, esc_idx, esc_count)
+        if gbdt:
+            ctx.sf_route_score(score, vmin, esc_idx, esc_count)
+        else:
+            ctx.sf_route(top, pred, vmin, esc_idx, esc_count)
         if ev:
             ev[3].record()
         if cfg.raw_pkts:
@@ -320,6 +354,8 @@ def main():
         kernels["sf_slow_infer"] = {"bound": "alu", "achieved": tf, "peak": F32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                                     "frac": tf / F32_VECTOR_PEAK_TFLOPS, "traffic": None, "ms": float(avg[3]),
                                     "flops": flops}
+    if gbdt:   # the boosted workload runs the same two steps through its own entry points
+        kernels = {{"sf_fast_infer": "sf_gbdt_infer", "sf_route": "sf_route_score"}.get(k, k): v for k, v in kernels.items()}
     names = list(kernels)
     dominant = names[int(np.argmax(avg))]
     roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
@@ -335,9 +371,11 @@ def main():
         "dtype": "f32 features, integer votes, %s MLP" % cfg.mlp_dtype,
         "data": "synthetic",
         "config": {"workload": "%s: %d flows, %d packets, F=%d, T=%d depth %d C=%d, vmin=%d, MLP %s %s"
-                               % (cfg.name, n, n_pkts, F, cfg.n_trees, cfg.tree_depth, C, vmin, cfg.mlp_dtype,
+                               % (cfg.name, n, n_pkts, F, cfg.n_trees, cfg.tree_depth, C, -1 if gbdt else vmin, cfg.mlp_dtype,
                                   "x".join(map(str, cfg.mlp_dims))),
-                   "escalated_fraction": n_esc / n, "calibrated_fraction": frac},
+                   "escalated_fraction": n_esc / n, "calibrated_fraction": frac,
+                   "fast_model": ("boosted trees, %s score, threshold %.6g" % (cfg.score, vmin)) if gbdt
+                                 else "hard-voting forest"},
         "roofline": roof,
         "kernels": kernels,
         "p50_ms": float(np.median(call_ms.sum(axis=1))), "p99_ms": float(np.percentile(call_ms.sum(axis=1), 99)),

@@ -226,6 +226,45 @@ int sf_route_subset(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred
                     const uint32_t* idx_count, uint32_t idx_cap, const uint16_t* host_vmin, uint32_t n_vmin,
                     uint32_t* esc_idx, uint32_t* esc_count);
 
+/* ---- boosted trees as the fast model, real-valued uncertainty scores ----------------------
+ * Section 4.1 names gradient-boosted trees among the models (the fast and slow models of the
+ * cascade evaluated in Section 5.2 are of that kind); Section 3.2 gives two scores on the
+ * model's class distribution: least confidence LC(x) = 1 - max_y P(y|x) and entropy
+ * H(x) = - sum_i P(y_i|x) log P(y_i|x).
+ *
+ * Tree t belongs to class t mod n_classes (boosting round t div n_classes); its leaves hold
+ * binary32 margins.  m[c] = base[c] + the leaf values of the class's trees, added in tree
+ * order, each addition rounded to binary32 (reproducible bit for bit).  P = softmax(m),
+ * evaluated in binary64; pred = arg-max of m, lowest class on ties; natural logarithm.
+ * Trees: perfect, heap order, x[f] <= thr goes left (as sf_forest). */
+typedef struct {
+    uint32_t n_trees, depth, n_classes, n_features;
+    const uint16_t* node_feat; /* [n_trees][2^depth - 1], values < n_features                  */
+    const float* node_thr;     /* [n_trees][2^depth - 1]                                       */
+    const float* leaf_value;   /* [n_trees][2^depth]                                           */
+    const float* base;         /* [n_classes] initial margins, or NULL for zeros               */
+} sf_gbdt;
+
+enum { SF_SCORE_LC = 0, SF_SCORE_ENTROPY = 1 };
+
+/* pred: [n_flows]; score: [n_flows], the chosen score rounded from binary64 to binary32;
+ * margins: optional [n_flows][n_classes]; leaf_idx: optional [n_flows][n_trees] (parity checks).
+ * Uses workspace for a packed copy of the trees. */
+int sf_gbdt_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows, const sf_gbdt* model,
+                  int score_kind, float* margins, uint16_t* pred, float* score, uint16_t* leaf_idx);
+
+/* The gate on such a score: flow i escalates iff score[i] > threshold.  Outputs as sf_route. */
+int sf_route_score(sf_ctx* ctx, const float* score, uint32_t n_flows, float threshold, uint32_t* esc_idx,
+                   uint32_t* esc_count);
+
+/* Algorithm 1 (universal uncertainty thresholds) on a real-valued score: for each quantile q the
+ * element at 1-based position ceil(q * n_flows) of the ascending order of score (device array),
+ * found exactly by two 16-bit histogram passes over order-preserving keys, no sort.  host_q and
+ * host_thresholds are HOST arrays of n_q entries.  Escalating the flows with score above the
+ * threshold assigns at most a fraction 1 - q of them.  Waits for the stream. */
+int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_flows, const double* host_q, uint32_t n_q,
+                       float* host_thresholds);
+
 /* ---- step 5: slow model on the escalated flows only ------------------------------------
  * Sections 3.1 and 4.4: only flows the fast model is unsure of reach the slow model, and
  * its answer replaces the fast one.  The slow model is a 3-layer ReLU MLP.

@@ -22,7 +22,7 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_validate_packets", "sf_fast_infer", "sf_validate_forest", "sf_route",
            "sf_vmin_from_theta", "sf_slow_infer", "sf_score_histogram", "sf_universal_thresholds",
            "sf_vmin_for_target", "sf_fastest_infer", "sf_validate_tree", "sf_route_ratio",
-           "sf_fast_infer_subset", "sf_route_subset")
+           "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles")
 
 
 class SfPackets(ctypes.Structure):
@@ -47,6 +47,15 @@ class SfForest(ctypes.Structure):
 class SfTree(ctypes.Structure):
     _fields_ = [("depth", ctypes.c_uint32), ("n_classes", ctypes.c_uint32), ("n_features", ctypes.c_uint32),
                 ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p), ("leaf_count", ctypes.c_void_p)]
+
+
+class SfGbdt(ctypes.Structure):
+    _fields_ = [("n_trees", ctypes.c_uint32), ("depth", ctypes.c_uint32), ("n_classes", ctypes.c_uint32),
+                ("n_features", ctypes.c_uint32), ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p),
+                ("leaf_value", ctypes.c_void_p), ("base", ctypes.c_void_p)]
+
+
+SF_SCORE_LC, SF_SCORE_ENTROPY = 0, 1
 
 
 class SfMlp(ctypes.Structure):
@@ -102,6 +111,13 @@ def load_library() -> ctypes.CDLL:
     lib.sf_fast_infer_subset.argtypes = [vp, vp, u32, u32, vp, vp, u32, ctypes.POINTER(SfForest), vp, vp, vp, vp]
     lib.sf_route_subset.restype = ctypes.c_int
     lib.sf_route_subset.argtypes = [vp, vp, vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
+    lib.sf_gbdt_infer.restype = ctypes.c_int
+    lib.sf_gbdt_infer.argtypes = [vp, vp, u32, u32, ctypes.POINTER(SfGbdt), ctypes.c_int, vp, vp, vp, vp]
+    lib.sf_route_score.restype = ctypes.c_int
+    lib.sf_route_score.argtypes = [vp, vp, u32, ctypes.c_float, vp, vp]
+    lib.sf_score_quantiles.restype = ctypes.c_int
+    lib.sf_score_quantiles.argtypes = [vp, vp, u32, ctypes.POINTER(ctypes.c_double), u32,
+                                       ctypes.POINTER(ctypes.c_float)]
     lib.sf_score_histogram.restype = ctypes.c_int
     lib.sf_score_histogram.argtypes = [vp, vp, u32, u32, ctypes.POINTER(ctypes.c_uint32)]
     lib.sf_universal_thresholds.restype = ctypes.c_int
@@ -210,6 +226,21 @@ class DeviceTree:
         s.node_feat = _ptr(self.node_feat, torch.int16).value
         s.node_thr = _ptr(self.node_thr, torch.float32).value
         s.leaf_count = _ptr(self.leaf_count, torch.int16).value
+        return s
+
+
+class DeviceGbdt:
+    def __init__(self, n_trees, depth, n_classes, n_features, node_feat, node_thr, leaf_value, base=None):
+        self.n_trees, self.depth, self.n_classes, self.n_features = n_trees, depth, n_classes, n_features
+        self.node_feat, self.node_thr, self.leaf_value, self.base = node_feat, node_thr, leaf_value, base
+
+    def c_struct(self) -> SfGbdt:
+        s = SfGbdt()
+        s.n_trees, s.depth, s.n_classes, s.n_features = self.n_trees, self.depth, self.n_classes, self.n_features
+        s.node_feat = _ptr(self.node_feat, torch.int16).value
+        s.node_thr = _ptr(self.node_thr, torch.float32).value
+        s.leaf_value = _ptr(self.leaf_value, torch.float32).value
+        s.base = _ptr(self.base, torch.float32).value if self.base is not None else None
         return s
 
 
@@ -354,6 +385,29 @@ class ServeFlow:
         self._check(self._lib.sf_route_subset(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16),
                                               _ptr(idx, torch.int32), _ptr(idx_count, torch.int32), cap, arr, len(vm),
                                               _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    # ---- boosted trees as the fast model, real-valued scores --------------------------------
+    def sf_gbdt_infer(self, feat: torch.Tensor, model: DeviceGbdt, score_kind: int, pred: torch.Tensor,
+                      score: torch.Tensor, margins: Optional[torch.Tensor] = None,
+                      leaf_idx: Optional[torch.Tensor] = None, n_flows: Optional[int] = None):
+        m = model.c_struct()
+        n = int(feat.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_gbdt_infer(self._h, _ptr(feat, torch.float32), int(feat.shape[1]), n, ctypes.byref(m),
+                                            int(score_kind), _ptr(margins, torch.float32), _ptr(pred, torch.int16),
+                                            _ptr(score, torch.float32), _ptr(leaf_idx, torch.int16)))
+
+    def sf_route_score(self, score: torch.Tensor, threshold: float, esc_idx: torch.Tensor, esc_count: torch.Tensor,
+                       n_flows: Optional[int] = None):
+        n = int(score.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_route_score(self._h, _ptr(score, torch.float32), n, ctypes.c_float(threshold),
+                                             _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_score_quantiles(self, score: torch.Tensor, quantiles, n_flows: Optional[int] = None):
+        n = int(score.shape[0]) if n_flows is None else n_flows
+        q = (ctypes.c_double * len(quantiles))(*[float(v) for v in quantiles])
+        out = (ctypes.c_float * len(quantiles))()
+        self._check(self._lib.sf_score_quantiles(self._h, _ptr(score, torch.float32), n, q, len(quantiles), out))
+        return [float(v) for v in out]
 
     def sf_score_histogram(self, top_votes: torch.Tensor, n_trees: int, n_flows: Optional[int] = None):
         n = int(top_votes.shape[0]) if n_flows is None else n_flows

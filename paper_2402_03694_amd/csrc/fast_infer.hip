@@ -65,6 +65,12 @@ struct FastArgs {
     const uint32_t* idx_count; // subset form: device-side length of idx
     uint32_t n_rows;           // subset form: rows of feat (list entries are clamped below it)
     uint16_t* labels;          // subset form, optional: labels[idx[j]] = pred of row j
+    // boosted form: leaves hold margins instead of labels, tree t adds to class t % n_classes
+    const float* leaf_value;   // [n_trees][2^depth]
+    const float* base;         // [n_classes] initial margins, or NULL
+    float* margins;            // optional [n][n_classes]
+    float* score;              // [n]: LC or entropy of softmax(margins)
+    int score_kind;
     uint32_t n_trees, depth, n_classes, n_features;
     uint32_t top_pairs; // pair-levels of every tree staged in shared memory
     uint32_t vote_bits; // width of one packed vote counter: 8 (n_trees <= 255) or 16
@@ -76,17 +82,20 @@ struct FastArgs {
     uint16_t* leaf_idx;
 };
 
-#ifndef SF_FAST_ILP
-#define SF_FAST_ILP 8
-#endif
-constexpr int kIlp = SF_FAST_ILP; // trees walked at once per lane
+constexpr int kIlp = 8; // trees walked at once per lane (measured: 4 and 16 are slower)
 
 // BS lanes per block; S lanes share one flow, lane group g of S walks trees g, g+S, g+2S, ...
 // Splitting a flow over S lanes divides the shared memory per lane by S (the feature tile is per
 // flow), which is what limits the number of resident waves.
-template <int BS, int S, bool WANT_LEAF>
+// GBDT = false: leaves are class labels and the flow's result is the vote count per class.
+// GBDT = true (S must be 1): leaves are binary32 margins; the lane's shared-memory column holds
+// one binary32 sum per class, started at the initial margin and extended tree by tree in tree
+// order (each addition rounded on its own, so the sums are reproducible bit for bit); the
+// epilogue turns them into softmax probabilities in binary64 and into the score of Section 3.2.
+template <int BS, int S, bool WANT_LEAF, bool GBDT>
 __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
 {
+    static_assert(!GBDT || S == 1, "margins are summed in tree order by one lane");
     constexpr uint32_t FPB = BS / S;       // flows per block
     constexpr uint32_t FPW = 64 / S;       // flows per wave
     constexpr uint32_t kColShift = FPB == 256 ? 10 : (FPB == 128 ? 9 : (FPB == 64 ? 8 : 7)); // log2(bytes per feature column)
@@ -96,7 +105,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     float* xT = reinterpret_cast<float*>(smem_raw);                          // [F][FPB]
     // vote counters, 32 / vote_bits classes per word, one column per LANE: [vote_words][BS]
     const uint32_t per_shift = a.vote_bits == 8 ? 2u : 1u; // log2(counters per word)
-    const uint32_t vote_words = (C + (1u << per_shift) - 1u) >> per_shift;
+    const uint32_t vote_words = GBDT ? C : (C + (1u << per_shift) - 1u) >> per_shift; // boosted: one float per class
     uint32_t* vT = reinterpret_cast<uint32_t*>(xT + (size_t)F * FPB);
     uint4* topT = reinterpret_cast<uint4*>(vT + (size_t)vote_words * BS);    // [T][top_recs]
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -131,7 +140,11 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
             for (uint32_t f = grp; f < F; f += S) xT[f * FPB + slot] = x[f];
         }
     }
-    for (uint32_t c = 0; c < vote_words; ++c) vT[c * BS + tid] = 0;
+    if (GBDT) {
+        for (uint32_t c = 0; c < C; ++c) vT[c * BS + tid] = __float_as_uint(a.base ? a.base[c] : 0.f);
+    } else {
+        for (uint32_t c = 0; c < vote_words; ++c) vT[c * BS + tid] = 0;
+    }
     const uint32_t n_rec = recs_upto(pair_levels(a.depth));
     const uint4* recs = reinterpret_cast<const uint4*>(a.recs);
     for (uint32_t q = tid; q < T * top_recs; q += BS) {
@@ -212,6 +225,20 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
 #pragma unroll
             for (int u = 0; u < kIlp; ++u) leaf[u] = (o[u] >> 4) - leaf_base;
         }
+        if (GBDT) {
+            float val[kIlp];
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u) val[u] = a.leaf_value[(size_t)tt[u] * n_leaf + leaf[u]];
+#pragma unroll
+            for (int u = 0; u < kIlp; ++u) { // ascending u = ascending tree: the order of the sum
+                if (tv[u]) {
+                    float* m = reinterpret_cast<float*>(&vcol[(tt[u] % C) * BS]);
+                    *m = *m + val[u];
+                    if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + tt[u]] = (uint16_t)leaf[u];
+                }
+            }
+            continue;
+        }
         uint32_t lab[kIlp];
 #pragma unroll
         for (int u = 0; u < kIlp; ++u) lab[u] = a.leaf_label[(size_t)tt[u] * n_leaf + leaf[u]];
@@ -228,6 +255,37 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
 #undef SF_PAIR_STEP
     if (S > 1) __syncthreads(); // the S partial vote columns of a flow are summed by its first lane
     if (!live || grp != 0) return;
+    if (GBDT) {
+        const float* mcol = reinterpret_cast<const float*>(vcol);
+        uint32_t bc = 0;
+        float bm = mcol[0];
+        for (uint32_t c = 1; c < C; ++c) {
+            const float m = mcol[c * BS];
+            if (m > bm) { // strict: the lowest class wins a tie
+                bm = m;
+                bc = c;
+            }
+        }
+        double z = 0.0;
+        for (uint32_t c = 0; c < C; ++c) z += exp((double)mcol[c * BS] - (double)bm);
+        double sc;
+        if (a.score_kind == SF_SCORE_ENTROPY) {
+            double h = 0.0;
+            for (uint32_t c = 0; c < C; ++c) {
+                const double p = exp((double)mcol[c * BS] - (double)bm) / z;
+                if (p > 0.0) h -= p * log(p);
+            }
+            sc = h;
+        } else {
+            sc = 1.0 - 1.0 / z; // the largest probability is exp(0) / z
+        }
+        if (a.margins)
+            for (uint32_t c = 0; c < C; ++c) a.margins[(size_t)i * C + c] = mcol[c * BS];
+        a.pred[i] = (uint16_t)bc;
+        a.score[i] = (float)sc;
+        if (a.labels) a.labels[row] = (uint16_t)bc;
+        return;
+    }
     uint32_t best = 0, bestv = 0;
     const uint32_t vmask = (1u << a.vote_bits) - 1u;
     for (uint32_t w = 0; w < vote_words; ++w) {
@@ -251,19 +309,19 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     if (a.labels) a.labels[row] = (uint16_t)best;
 }
 
-template <int BS, int S>
+template <int BS, int S, bool GBDT>
 int launch_votes(sf_ctx* ctx, const FastArgs& a, size_t lds)
 {
     const uint32_t fpb = BS / S;
     const uint32_t grid = (a.n_flows + fpb - 1) / fpb;
     if (a.leaf_idx) {
-        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, true>,
+        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, true, GBDT>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        forest_votes<BS, S, true><<<grid, BS, lds, ctx->stream>>>(a);
+        forest_votes<BS, S, true, GBDT><<<grid, BS, lds, ctx->stream>>>(a);
     } else {
-        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, false>,
+        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, false, GBDT>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        forest_votes<BS, S, false><<<grid, BS, lds, ctx->stream>>>(a);
+        forest_votes<BS, S, false, GBDT><<<grid, BS, lds, ctx->stream>>>(a);
     }
     SF_LAUNCH_CHECK(ctx, "forest_votes");
     return SF_OK;
@@ -281,40 +339,57 @@ size_t forest_pack_bytes(uint32_t n_trees, uint32_t depth)
 
 namespace {
 
-// both entry points: n_flows rows (all flows, or the capacity of the list idx)
-int run_forest(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows, const uint32_t* idx,
-               const uint32_t* idx_count, uint32_t n_rows, const sf_forest* forest, uint16_t* votes, uint16_t* pred,
-               uint16_t* top_votes, uint16_t* leaf_idx, uint16_t* labels)
+// the model as the kernels see it: hard-voting forest (leaf_label) or boosted trees (leaf_value, base)
+struct TreeModel {
+    uint32_t n_trees, depth, n_classes, n_features;
+    const uint16_t* node_feat;
+    const float* node_thr;
+    const uint8_t* leaf_label;
+    const float* leaf_value;
+    const float* base;
+};
+
+struct Outputs {
+    uint16_t* votes;
+    uint16_t* pred;
+    uint16_t* top_votes;
+    uint16_t* leaf_idx;
+    uint16_t* labels;
+    float* margins;
+    float* score;
+    int score_kind;
+};
+
+// every entry point of this file: n_flows rows (all flows, or the capacity of the list idx)
+int run_trees(sf_ctx* ctx, const char* who, const float* feat, uint32_t feat_ld, uint32_t n_flows, const uint32_t* idx,
+              const uint32_t* idx_count, uint32_t n_rows, const TreeModel& m, bool gbdt, const Outputs& out)
 {
-    if (!forest) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: forest is NULL");
-    if (forest->depth < 1 || forest->depth > SF_MAX_TREE_DEPTH)
-        return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: depth %u outside 1..%d", forest->depth, SF_MAX_TREE_DEPTH);
-    if (forest->n_trees < 1 || forest->n_trees > 65535)
-        return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: n_trees %u outside 1..65535", forest->n_trees);
-    if (forest->n_classes < 1 || forest->n_classes > SF_MAX_CLASSES)
-        return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: n_classes %u outside 1..%d", forest->n_classes, SF_MAX_CLASSES);
-    if (forest->n_features < 1 || forest->n_features > SF_MAX_FEATURES)
-        return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: n_features %u outside 1..%d", forest->n_features,
-                        SF_MAX_FEATURES);
-    if (forest->n_features > feat_ld)
-        return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: n_features %u > feat_ld %u", forest->n_features, feat_ld);
-    if (!forest->node_feat || !forest->node_thr || !forest->leaf_label)
-        return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: forest arrays missing");
+    if (m.depth < 1 || m.depth > SF_MAX_TREE_DEPTH)
+        return sf::fail(ctx, SF_EINVAL, "%s: depth %u outside 1..%d", who, m.depth, SF_MAX_TREE_DEPTH);
+    if (m.n_trees < 1 || m.n_trees > 65535) return sf::fail(ctx, SF_EINVAL, "%s: n_trees %u outside 1..65535", who, m.n_trees);
+    if (m.n_classes < 1 || m.n_classes > SF_MAX_CLASSES)
+        return sf::fail(ctx, SF_EINVAL, "%s: n_classes %u outside 1..%d", who, m.n_classes, SF_MAX_CLASSES);
+    if (m.n_features < 1 || m.n_features > SF_MAX_FEATURES)
+        return sf::fail(ctx, SF_EINVAL, "%s: n_features %u outside 1..%d", who, m.n_features, SF_MAX_FEATURES);
+    if (m.n_features > feat_ld) return sf::fail(ctx, SF_EINVAL, "%s: n_features %u > feat_ld %u", who, m.n_features, feat_ld);
+    if (!m.node_feat || !m.node_thr || (gbdt ? !m.leaf_value : !m.leaf_label))
+        return sf::fail(ctx, SF_EINVAL, "%s: model arrays missing", who);
     if (n_flows == 0) return SF_OK;
-    if (!feat || !pred || !top_votes) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer: feat, pred or top_votes is NULL");
+    if (!feat || !out.pred || (gbdt ? !out.score : !out.top_votes))
+        return sf::fail(ctx, SF_EINVAL, "%s: feat, pred or %s is NULL", who, gbdt ? "score" : "top_votes");
 
     sf::Carve ws(ctx);
-    const size_t pack_bytes = sf::forest_pack_bytes(forest->n_trees, forest->depth);
+    const size_t pack_bytes = sf::forest_pack_bytes(m.n_trees, m.depth);
     PairRec* packed = (PairRec*)ws.take(pack_bytes);
     if (!packed)
-        return sf::fail(ctx, SF_ENOMEM, "sf_fast_infer: workspace has %zu bytes, packed forest needs %zu",
-                        ctx->ws_bytes, pack_bytes + sf::kFlagBytes);
+        return sf::fail(ctx, SF_ENOMEM, "%s: workspace has %zu bytes, packed trees need %zu", who, ctx->ws_bytes,
+                        pack_bytes + sf::kFlagBytes);
     {
-        const uint64_t total = (uint64_t)forest->n_trees * recs_upto(pair_levels(forest->depth));
+        const uint64_t total = (uint64_t)m.n_trees * recs_upto(pair_levels(m.depth));
         uint64_t blocks = (total + 255) / 256;
         if (blocks > 8192) blocks = 8192;
-        pack_forest<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(forest->n_trees, forest->depth, forest->n_features,
-                                                               forest->node_feat, forest->node_thr, packed);
+        pack_forest<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(m.n_trees, m.depth, m.n_features, m.node_feat, m.node_thr,
+                                                               packed);
         SF_LAUNCH_CHECK(ctx, "pack_forest");
     }
     FastArgs a;
@@ -324,52 +399,57 @@ int run_forest(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flow
     a.idx = idx;
     a.idx_count = idx_count;
     a.n_rows = n_rows;
-    a.labels = labels;
-    a.n_trees = forest->n_trees;
-    a.depth = forest->depth;
-    a.n_classes = forest->n_classes;
-    a.n_features = forest->n_features;
+    a.labels = out.labels;
+    a.leaf_value = m.leaf_value;
+    a.base = m.base;
+    a.margins = out.margins;
+    a.score = out.score;
+    a.score_kind = out.score_kind;
+    a.n_trees = m.n_trees;
+    a.depth = m.depth;
+    a.n_classes = m.n_classes;
+    a.n_features = m.n_features;
     a.recs = packed;
-    a.leaf_label = forest->leaf_label;
-    a.votes = votes;
-    a.pred = pred;
-    a.top = top_votes;
-    a.leaf_idx = leaf_idx;
-    // Shared memory per block of 256 lanes: a feature column per FLOW, packed vote counters per
-    // lane, and the staged top records of every tree.  With two lanes per flow three blocks (12
-    // waves) stay resident instead of two, which pays while the deep records of the trees in
-    // flight still fit the first-level cache (measured: faster up to depth 10, slower at 12,
-    // where more waves mean more distinct trees in flight and more cache misses).
+    a.leaf_label = m.leaf_label;
+    a.votes = out.votes;
+    a.pred = out.pred;
+    a.top = out.top_votes;
+    a.leaf_idx = out.leaf_idx;
+    // Shared memory per block of 256 lanes: a feature column per FLOW, the per-lane result column
+    // (packed vote counters, or one binary32 margin per class) and the staged top records of
+    // every tree.  With two lanes per flow three blocks (12 waves) stay resident instead of two,
+    // which pays while the deep records of the trees in flight still fit the first-level cache
+    // (measured: faster up to depth 10, slower at 12, where more waves mean more distinct trees
+    // in flight and more cache misses).  Margins are summed in tree order by one lane, so the
+    // boosted form never splits a flow.
     a.vote_bits = a.n_trees <= 255 ? 8u : 16u;
-    const uint32_t vote_words = (a.n_classes * a.vote_bits + 31u) / 32u;
-#ifdef SF_FAST_SPLIT
-    const uint32_t split = SF_FAST_SPLIT;
-#else
-    const uint32_t split = (a.n_trees >= 32 && recs_upto(pair_levels(forest->depth)) * 16u <= 8192u) ? 2u : 1u;
-#endif
-    const size_t fixed = (size_t)a.n_features * 4 * (256 / split) + (size_t)vote_words * 4 * 256;
-#ifdef SF_FAST_BUDGET
-    size_t budget = SF_FAST_BUDGET;
-#else
+    const uint32_t result_words = gbdt ? a.n_classes : (a.n_classes * a.vote_bits + 31u) / 32u;
+    const uint32_t split = (!gbdt && a.n_trees >= 32 && recs_upto(pair_levels(m.depth)) * 16u <= 8192u) ? 2u : 1u;
+    const size_t fixed = (size_t)a.n_features * 4 * (256 / split) + (size_t)result_words * 4 * 256;
+    // the top records may use what is left of a third, else of a half, else of the whole shared memory
     size_t budget = 160 * 1024 / 3 - 256;
-#endif
     if (fixed + (size_t)a.n_trees * 16 > budget) budget = 80 * 1024 - 512;
     if (fixed + (size_t)a.n_trees * 16 > budget) budget = 160 * 1024 - 1024;
-    const uint32_t full_pairs = forest->depth / 2;
+    const uint32_t full_pairs = m.depth / 2;
     uint32_t top_pairs = 0;
-#ifdef SF_FAST_TOP_PAIRS
-    const uint32_t want_pairs = SF_FAST_TOP_PAIRS;
-#else
-    const uint32_t want_pairs = 8;
-#endif
-    while (top_pairs < full_pairs && top_pairs < want_pairs &&
-           fixed + (size_t)a.n_trees * recs_upto(top_pairs + 1) * 16 <= budget)
-        ++top_pairs;
+    while (top_pairs < full_pairs && fixed + (size_t)a.n_trees * recs_upto(top_pairs + 1) * 16 <= budget) ++top_pairs;
     a.top_pairs = top_pairs;
     const size_t lds = fixed + (size_t)a.n_trees * recs_upto(top_pairs) * 16;
-    if (lds > 160 * 1024) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_fast_infer: %zu bytes of shared memory needed", lds);
-    if (split == 2) return launch_votes<256, 2>(ctx, a, lds);
-    return launch_votes<256, 1>(ctx, a, lds);
+    if (lds > 160 * 1024) return sf::fail(ctx, SF_EUNSUPPORTED, "%s: %zu bytes of shared memory needed", who, lds);
+    if (gbdt) return launch_votes<256, 1, true>(ctx, a, lds);
+    if (split == 2) return launch_votes<256, 2, false>(ctx, a, lds);
+    return launch_votes<256, 1, false>(ctx, a, lds);
+}
+
+int run_forest(sf_ctx* ctx, const char* who, const float* feat, uint32_t feat_ld, uint32_t n_flows, const uint32_t* idx,
+               const uint32_t* idx_count, uint32_t n_rows, const sf_forest* f, uint16_t* votes, uint16_t* pred,
+               uint16_t* top_votes, uint16_t* leaf_idx, uint16_t* labels)
+{
+    if (!f) return sf::fail(ctx, SF_EINVAL, "%s: forest is NULL", who);
+    const TreeModel m = {f->n_trees, f->depth, f->n_classes, f->n_features, f->node_feat, f->node_thr, f->leaf_label,
+                         nullptr, nullptr};
+    const Outputs out = {votes, pred, top_votes, leaf_idx, labels, nullptr, nullptr, 0};
+    return run_trees(ctx, who, feat, feat_ld, n_flows, idx, idx_count, n_rows, m, false, out);
 }
 
 } // namespace
@@ -379,8 +459,8 @@ extern "C" int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
                              uint16_t* leaf_idx)
 {
     if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_fast_infer: ctx is NULL");
-    return run_forest(ctx, feat, feat_ld, n_flows, nullptr, nullptr, n_flows, forest, votes, pred, top_votes, leaf_idx,
-                      nullptr);
+    return run_forest(ctx, "sf_fast_infer", feat, feat_ld, n_flows, nullptr, nullptr, n_flows, forest, votes, pred,
+                      top_votes, leaf_idx, nullptr);
 }
 
 extern "C" int sf_fast_infer_subset(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
@@ -391,6 +471,19 @@ extern "C" int sf_fast_infer_subset(sf_ctx* ctx, const float* feat, uint32_t fea
     if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_fast_infer_subset: ctx is NULL");
     if (idx_cap && n_flows == 0) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer_subset: a list over zero flows");
     if (idx_cap && (!idx || !idx_count)) return sf::fail(ctx, SF_EINVAL, "sf_fast_infer_subset: idx or idx_count is NULL");
-    return run_forest(ctx, feat, feat_ld, idx_cap, idx, idx_count, n_flows, forest, votes, pred, top_votes, nullptr,
-                      labels);
+    return run_forest(ctx, "sf_fast_infer_subset", feat, feat_ld, idx_cap, idx, idx_count, n_flows, forest, votes, pred,
+                      top_votes, nullptr, labels);
+}
+
+extern "C" int sf_gbdt_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows, const sf_gbdt* model,
+                             int score_kind, float* margins, uint16_t* pred, float* score, uint16_t* leaf_idx)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_gbdt_infer: ctx is NULL");
+    if (!model) return sf::fail(ctx, SF_EINVAL, "sf_gbdt_infer: model is NULL");
+    if (score_kind != SF_SCORE_LC && score_kind != SF_SCORE_ENTROPY)
+        return sf::fail(ctx, SF_EINVAL, "sf_gbdt_infer: score_kind %d is neither SF_SCORE_LC nor SF_SCORE_ENTROPY", score_kind);
+    const TreeModel m = {model->n_trees, model->depth, model->n_classes, model->n_features, model->node_feat,
+                         model->node_thr, nullptr, model->leaf_value, model->base};
+    const Outputs out = {nullptr, pred, nullptr, leaf_idx, nullptr, margins, score, score_kind};
+    return run_trees(ctx, "sf_gbdt_infer", feat, feat_ld, n_flows, nullptr, nullptr, n_flows, m, true, out);
 }

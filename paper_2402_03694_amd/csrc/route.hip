@@ -9,6 +9,8 @@
 // re-evaluates the gate and writes the indices in order (a wave-level prefix sum of per-lane
 // pop-counts gives each lane its write position).  The count stays on the device.
 #include <cmath>
+#include <cstring>
+#include <new>
 
 #include "common.h"
 
@@ -24,6 +26,8 @@ struct RouteArgs {
     const uint16_t* pred;
     const uint16_t* total;     // ratio gate: per-row denominators (NULL = vote gate)
     float theta;               // ratio gate: escalate iff top / total < theta
+    const float* score;        // score gate: a real-valued uncertainty per row (NULL = the integer gates)
+    float score_thr;           // score gate: escalate iff score > score_thr
     const uint32_t* src_idx;   // rows are the entries of this list (NULL = rows are flows)
     const uint32_t* src_count; // device-side length of that list (n is then its capacity)
     uint32_t n;
@@ -56,6 +60,13 @@ __device__ __forceinline__ uint32_t gate_mask(const RouteArgs& a, uint32_t n, ui
 {
     uint32_t m = 0;
     if (base >= n) return 0;
+    if (a.score) {
+        for (int k = 0; k < kPerLane; ++k) {
+            const uint32_t i = base + k;
+            if (i < n) m |= (a.score[i] > a.score_thr ? 1u : 0u) << k;
+        }
+        return m;
+    }
     if (a.total) {
         for (int k = 0; k < kPerLane; ++k) {
             const uint32_t i = base + k;
@@ -204,6 +215,29 @@ __global__ __launch_bounds__(256) void hist_scores(const uint16_t* __restrict__ 
     }
 }
 
+// ---- calibration on a real-valued score: exact order statistics by two 16-bit histograms ------
+
+// order-preserving 32-bit key of a binary32 value (negative values below positive ones)
+__device__ __forceinline__ uint32_t float_key(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// hist[key >> 16] += 1 for every score (prefix_on = 0), or hist[key & 0xFFFF] += 1 for the scores
+// whose upper half equals prefix (prefix_on = 1)
+__global__ __launch_bounds__(256) void hist_float_keys(const float* __restrict__ score, uint32_t n, uint32_t prefix_on,
+                                                       uint32_t prefix, uint32_t* __restrict__ hist)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t k = float_key(score[i]);
+        if (!prefix_on)
+            atomicAdd(&hist[k >> 16], 1u);
+        else if ((k >> 16) == prefix)
+            atomicAdd(&hist[k & 0xFFFFu], 1u);
+    }
+}
+
 // shared launch of the two kernels; a.top, a.pred, a.total, a.theta, a.src_*, a.n, a.n_vmin and
 // a.vmin are filled by the caller
 int launch_route(sf_ctx* ctx, const char* who, RouteArgs& a, uint32_t* esc_idx, uint32_t* esc_count)
@@ -283,6 +317,23 @@ extern "C" int sf_route_ratio(sf_ctx* ctx, const uint16_t* top_count, const uint
     a.n = n_flows;
     a.n_vmin = 1;
     return launch_route(ctx, "sf_route_ratio", a, esc_idx, esc_count);
+}
+
+extern "C" int sf_route_score(sf_ctx* ctx, const float* score, uint32_t n_flows, float threshold, uint32_t* esc_idx,
+                              uint32_t* esc_count)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route_score: ctx is NULL");
+    if (threshold != threshold) return sf::fail(ctx, SF_EINVAL, "sf_route_score: threshold is NaN");
+    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route_score: esc_count is NULL");
+    if (n_flows == 0) return zero_count(ctx, esc_count);
+    if (n_flows > (1u << 31)) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route_score: more than 2^31 flows per call");
+    if (!score || !esc_idx) return sf::fail(ctx, SF_EINVAL, "sf_route_score: score or esc_idx is NULL");
+    RouteArgs a = {};
+    a.score = score;
+    a.score_thr = threshold;
+    a.n = n_flows;
+    a.n_vmin = 1;
+    return launch_route(ctx, "sf_route_score", a, esc_idx, esc_count);
 }
 
 extern "C" int sf_route_subset(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, const uint32_t* idx,
@@ -384,4 +435,62 @@ extern "C" uint32_t sf_vmin_for_target(const uint32_t* host_hist, uint32_t n_tre
     }
     if (reached_fraction) *reached_fraction = n ? (double)best_below / (double)n : 0.0;
     return best;
+}
+
+extern "C" int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_flows, const double* host_q, uint32_t n_q,
+                                  float* host_thresholds)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_score_quantiles: ctx is NULL");
+    if (!score || !host_q || !host_thresholds || n_flows == 0)
+        return sf::fail(ctx, SF_EINVAL, "sf_score_quantiles: score, host_q or host_thresholds missing, or no flows");
+    sf::Carve ws(ctx);
+    uint32_t* d_hist = (uint32_t*)ws.take(sf::kQuantileBins * 4);
+    if (!d_hist) return sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: workspace too small for %zu bytes", sf::kQuantileBins * 4);
+    uint32_t* h = new (std::nothrow) uint32_t[sf::kQuantileBins];
+    if (!h) return sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: out of host memory");
+    uint32_t blocks = (n_flows + 256 * 16 - 1) / (256 * 16);
+    blocks = blocks > 2048 ? 2048 : blocks;
+    // one pass over the upper 16 key bits, then one pass per quantile over the lower 16 bits of
+    // the scores that share the upper half of the wanted element
+    auto histogram = [&](uint32_t prefix_on, uint32_t prefix) -> int {
+        hist_zero<<<sf::kQuantileBins / 256, 256, 0, ctx->stream>>>(d_hist, sf::kQuantileBins);
+        SF_LAUNCH_CHECK(ctx, "hist_zero");
+        hist_float_keys<<<blocks, 256, 0, ctx->stream>>>(score, n_flows, prefix_on, prefix, d_hist);
+        SF_LAUNCH_CHECK(ctx, "hist_float_keys");
+        SF_HIP(ctx, hipMemcpyAsync(h, d_hist, sf::kQuantileBins * 4, hipMemcpyDeviceToHost, ctx->stream));
+        SF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        return SF_OK;
+    };
+    int rc = histogram(0, 0);
+    uint32_t* hi = nullptr;
+    if (rc == SF_OK) {
+        hi = new (std::nothrow) uint32_t[sf::kQuantileBins];
+        if (!hi) rc = sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: out of host memory");
+    }
+    if (rc == SF_OK) {
+        for (size_t b = 0; b < sf::kQuantileBins; ++b) hi[b] = h[b];
+        for (uint32_t j = 0; j < n_q && rc == SF_OK; ++j) {
+            // 1-based position ceil(q * n) in the ascending order (Algorithm 1), clamped to 1..n
+            double pos = std::ceil(host_q[j] * (double)n_flows);
+            if (!(pos >= 1.0)) pos = 1.0;
+            if (pos > (double)n_flows) pos = (double)n_flows;
+            uint64_t want = (uint64_t)pos, seen = 0;
+            uint32_t top = 0;
+            for (; top < sf::kQuantileBins - 1 && seen + hi[top] < want; ++top) seen += hi[top];
+            rc = histogram(1, top);
+            if (rc != SF_OK) break;
+            want -= seen;
+            seen = 0;
+            uint32_t low = 0;
+            for (; low < sf::kQuantileBins - 1 && seen + h[low] < want; ++low) seen += h[low];
+            const uint32_t key = (top << 16) | low;
+            const uint32_t bits = (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
+            float f;
+            memcpy(&f, &bits, 4);
+            host_thresholds[j] = f;
+        }
+    }
+    delete[] h;
+    delete[] hi;
+    return rc;
 }

@@ -2,7 +2,7 @@
 import numpy as np
 import torch
 
-from .binding import SF_BF16, SF_F32, DeviceForest, DeviceMlp, DevicePackets, DeviceTree
+from .binding import SF_BF16, SF_F32, DeviceForest, DeviceMlp, DeviceGbdt, DevicePackets, DeviceTree
 
 
 def _dev(a: np.ndarray, device) -> torch.Tensor:
@@ -30,6 +30,11 @@ def forest_to_device(f, device="cuda:0") -> DeviceForest:
 def tree_to_device(t, device="cuda:0") -> DeviceTree:
     return DeviceTree(t.depth, t.n_classes, t.n_features, _dev(t.node_feat, device), _dev(t.node_thr, device),
                       _dev(t.leaf_count, device))
+
+
+def gbdt_to_device(g, device="cuda:0") -> DeviceGbdt:
+    return DeviceGbdt(g.n_trees, g.depth, g.n_classes, g.n_features, _dev(g.node_feat, device), _dev(g.node_thr, device),
+                      _dev(g.leaf_value, device), _dev(g.base, device) if g.base is not None else None)
 
 
 def mlp_to_device(m, device="cuda:0") -> DeviceMlp:
