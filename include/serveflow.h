@@ -177,6 +177,24 @@ int sf_universal_thresholds(const uint32_t* host_hist, uint32_t n_trees, const d
 uint32_t sf_vmin_for_target(const uint32_t* host_hist, uint32_t n_trees, double target_fraction,
                             double* reached_fraction);
 
+/* Slope-based per-class thresholds (Section 3.2, Algorithm 2), for a validation set whose true labels
+ * are known.  sf_class_score_histogram: host_hist[((c * (n_trees+1)) + v) * 2 + w] (HOST memory,
+ * n_classes * (n_trees+1) * 2 words) = number of flows with pred == c, top_votes == v and w = 0 for a
+ * correct prediction (pred == truth), 1 for an incorrect one; top_votes, pred, truth are device arrays
+ * of n_flows entries.  Runs on the device, then waits for the stream.
+ *
+ * sf_per_class_thresholds (host function): every class starts with nothing assigned; a class's
+ * candidates are its non-empty vote counts, fewest votes (highest uncertainty) first; a candidate
+ * assigns dC correct and dI incorrect flows and has slope dI / (dC + dI); each increment takes the
+ * steepest next candidate over the classes (exact comparison; lowest class on ties) until the
+ * assigned total reaches target_fraction of the flows or nothing is left.  host_vmin[c] receives the
+ * class's threshold for sf_route's per-class form (flow escalates iff top_votes < host_vmin[pred]);
+ * *reached_fraction (optional) the assigned fraction. */
+int sf_class_score_histogram(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, const uint16_t* truth,
+                             uint32_t n_flows, uint32_t n_trees, uint32_t n_classes, uint32_t* host_hist);
+int sf_per_class_thresholds(const uint32_t* host_hist, uint32_t n_trees, uint32_t n_classes, double target_fraction,
+                            uint16_t* host_vmin, double* reached_fraction);
+
 /* ---- three tiers: a single decision tree in front of the fast model ----------------------
  * Section 3.1: a "fastest" model (a decision tree) sees every flow first; only the flows it
  * is unsure of go on to the fast model, and only those the fast model is unsure of reach the

@@ -195,6 +195,54 @@ def universal_thresholds(scores, quantiles) -> np.ndarray:
     return out
 
 
+def per_class_thresholds(pred, top_votes, correct, n_trees: int, n_classes: int, target_fraction: float):
+    """Slope-based per-class uncertainty thresholds (Algorithm 2) on the integer score.
+
+    Uncertainty is LC = 1 - top_votes / n_trees, so "most uncertain first" is "fewest votes first".
+    Reading of the algorithm's steps:
+      * per predicted class L the flows are split into correct and incorrect ones;
+      * the class's candidate thresholds are the distinct score values it contains (the finest quantile
+        grid); lowering the class's threshold by one candidate assigns the flows of the next vote count v:
+        dC correct and dI incorrect ones, slope = dI / (dC + dI);
+      * every class starts at its highest uncertainty (nothing assigned); each increment takes, among the
+        classes' next candidates, the one with the largest slope (exact comparison of the fractions; the
+        lowest class on ties), moves that class's threshold and adds dC + dI to the assigned total;
+      * increments stop as soon as the assigned total reaches target_fraction * N (or nothing is left).
+    Returns (vmin[C], assigned fraction, the list of (class, v, dC, dI) taken): class c escalates a flow
+    iff top_votes < vmin[c]."""
+    from fractions import Fraction
+    pred, top, correct = np.asarray(pred), np.asarray(top_votes), np.asarray(correct).astype(bool)
+    n = pred.shape[0]
+    steps = []                       # per class: list of (v, dC, dI) in order of decreasing uncertainty
+    for L in range(n_classes):
+        mine = pred == L
+        cand = []
+        for v in sorted(set(top[mine].tolist())):
+            sel = mine & (top == v)
+            cand.append((int(v), int((sel & correct).sum()), int((sel & ~correct).sum())))
+        steps.append(cand)
+    nxt = [0] * n_classes
+    vmin = [0] * n_classes
+    assigned, taken = 0, []
+    want = Fraction(float(target_fraction)) * n
+    while assigned < want:
+        best, best_slope = None, None
+        for L in range(n_classes):
+            if nxt[L] < len(steps[L]):
+                v, dc, di = steps[L][nxt[L]]
+                slope = Fraction(di, dc + di)
+                if best is None or slope > best_slope:
+                    best, best_slope = L, slope
+        if best is None:
+            break
+        v, dc, di = steps[best][nxt[best]]
+        nxt[best] += 1
+        vmin[best] = v + 1
+        assigned += dc + di
+        taken.append((best, v, dc, di))
+    return np.asarray(vmin, np.uint16), (assigned / n if n else 0.0), taken
+
+
 def slow_infer(esc_idx, mlp, n_flows: int, feat=None, flow_off=None, pkt_hdr=None, raw_pkts: int = 0,
                raw_bits: int = 0, labels: Optional[np.ndarray] = None, n_threads: int = 1):
     """mlp: any object with dims, dtype, w1..b3, mu, inv_sigma, clamp.  Returns (logits, labels);

@@ -22,7 +22,8 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_validate_packets", "sf_fast_infer", "sf_validate_forest", "sf_route",
            "sf_vmin_from_theta", "sf_slow_infer", "sf_score_histogram", "sf_universal_thresholds",
            "sf_vmin_for_target", "sf_fastest_infer", "sf_validate_tree", "sf_route_ratio",
-           "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles")
+           "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
+           "sf_class_score_histogram", "sf_per_class_thresholds")
 
 
 class SfPackets(ctypes.Structure):
@@ -111,6 +112,11 @@ def load_library() -> ctypes.CDLL:
     lib.sf_fast_infer_subset.argtypes = [vp, vp, u32, u32, vp, vp, u32, ctypes.POINTER(SfForest), vp, vp, vp, vp]
     lib.sf_route_subset.restype = ctypes.c_int
     lib.sf_route_subset.argtypes = [vp, vp, vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
+    lib.sf_class_score_histogram.restype = ctypes.c_int
+    lib.sf_class_score_histogram.argtypes = [vp, vp, vp, vp, u32, u32, u32, ctypes.POINTER(ctypes.c_uint32)]
+    lib.sf_per_class_thresholds.restype = ctypes.c_int
+    lib.sf_per_class_thresholds.argtypes = [ctypes.POINTER(ctypes.c_uint32), u32, u32, ctypes.c_double,
+                                            ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_double)]
     lib.sf_gbdt_infer.restype = ctypes.c_int
     lib.sf_gbdt_infer.argtypes = [vp, vp, u32, u32, ctypes.POINTER(SfGbdt), ctypes.c_int, vp, vp, vp, vp]
     lib.sf_route_score.restype = ctypes.c_int
@@ -169,6 +175,17 @@ def sf_universal_thresholds(hist, n_trees: int, quantiles):
     if rc != SF_OK:
         raise ServeFlowError(rc, "sf_universal_thresholds: bad arguments or empty histogram")
     return list(out)
+
+
+def sf_per_class_thresholds(hist, n_trees: int, n_classes: int, target: float):
+    """hist: the flat list from ServeFlow.sf_class_score_histogram.  Returns (vmin per class, reached fraction)."""
+    h = (ctypes.c_uint32 * len(hist))(*hist)
+    out = (ctypes.c_uint16 * n_classes)()
+    reached = ctypes.c_double()
+    rc = lib().sf_per_class_thresholds(h, n_trees, n_classes, float(target), out, ctypes.byref(reached))
+    if rc != SF_OK:
+        raise ServeFlowError(rc, "sf_per_class_thresholds: bad arguments")
+    return [int(v) for v in out], reached.value
 
 
 def sf_vmin_for_target(hist, n_trees: int, target: float):
@@ -408,6 +425,14 @@ class ServeFlow:
         out = (ctypes.c_float * len(quantiles))()
         self._check(self._lib.sf_score_quantiles(self._h, _ptr(score, torch.float32), n, q, len(quantiles), out))
         return [float(v) for v in out]
+
+    def sf_class_score_histogram(self, top_votes: torch.Tensor, pred: torch.Tensor, truth: torch.Tensor, n_trees: int,
+                                 n_classes: int, n_flows: Optional[int] = None):
+        n = int(top_votes.shape[0]) if n_flows is None else n_flows
+        hist = (ctypes.c_uint32 * (n_classes * (n_trees + 1) * 2))()
+        self._check(self._lib.sf_class_score_histogram(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16),
+                                                       _ptr(truth, torch.int16), n, n_trees, n_classes, hist))
+        return list(hist)
 
     def sf_score_histogram(self, top_votes: torch.Tensor, n_trees: int, n_flows: Optional[int] = None):
         n = int(top_votes.shape[0]) if n_flows is None else n_flows

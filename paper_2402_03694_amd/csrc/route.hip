@@ -215,6 +215,19 @@ __global__ __launch_bounds__(256) void hist_scores(const uint16_t* __restrict__ 
     }
 }
 
+// hist[((pred * bins) + top_votes) * 2 + wrong] += 1, wrong = (pred != truth); out-of-range values are clamped
+__global__ __launch_bounds__(256) void hist_class_scores(const uint16_t* __restrict__ top, const uint16_t* __restrict__ pred,
+                                                         const uint16_t* __restrict__ truth, uint32_t n, uint32_t bins,
+                                                         uint32_t n_classes, uint32_t* __restrict__ hist)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        uint32_t v = top[i], c = pred[i];
+        v = v < bins ? v : bins - 1u;
+        c = c < n_classes ? c : n_classes - 1u;
+        atomicAdd(&hist[((size_t)c * bins + v) * 2u + (pred[i] != truth[i] ? 1u : 0u)], 1u);
+    }
+}
+
 // ---- calibration on a real-valued score: exact order statistics by two 16-bit histograms ------
 
 // order-preserving 32-bit key of a binary32 value (negative values below positive ones)
@@ -493,4 +506,92 @@ extern "C" int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_fl
     delete[] h;
     delete[] hi;
     return rc;
+}
+
+extern "C" int sf_class_score_histogram(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, const uint16_t* truth,
+                                        uint32_t n_flows, uint32_t n_trees, uint32_t n_classes, uint32_t* host_hist)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_class_score_histogram: ctx is NULL");
+    if (!host_hist) return sf::fail(ctx, SF_EINVAL, "sf_class_score_histogram: host_hist is NULL");
+    if (n_trees < 1 || n_trees > 65535 || n_classes < 1 || n_classes > SF_MAX_CLASSES)
+        return sf::fail(ctx, SF_EINVAL, "sf_class_score_histogram: n_trees %u or n_classes %u out of range", n_trees, n_classes);
+    const size_t words = (size_t)n_classes * (n_trees + 1u) * 2u;
+    if (n_flows == 0) {
+        for (size_t b = 0; b < words; ++b) host_hist[b] = 0;
+        return SF_OK;
+    }
+    if (!top_votes || !pred || !truth) return sf::fail(ctx, SF_EINVAL, "sf_class_score_histogram: top_votes, pred or truth is NULL");
+    sf::Carve ws(ctx);
+    uint32_t* d_hist = (uint32_t*)ws.take(words * 4);
+    if (!d_hist) return sf::fail(ctx, SF_ENOMEM, "sf_class_score_histogram: workspace too small for %zu bytes", words * 4);
+    uint32_t zb = (uint32_t)((words + 255) / 256);
+    hist_zero<<<zb > 4096 ? 4096 : zb, 256, 0, ctx->stream>>>(d_hist, (uint32_t)words);
+    SF_LAUNCH_CHECK(ctx, "hist_zero");
+    uint32_t blocks = (n_flows + 256 * 16 - 1) / (256 * 16);
+    blocks = blocks > 2048 ? 2048 : blocks;
+    hist_class_scores<<<blocks, 256, 0, ctx->stream>>>(top_votes, pred, truth, n_flows, n_trees + 1u, n_classes, d_hist);
+    SF_LAUNCH_CHECK(ctx, "hist_class_scores");
+    SF_HIP(ctx, hipMemcpyAsync(host_hist, d_hist, words * 4, hipMemcpyDeviceToHost, ctx->stream));
+    SF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return SF_OK;
+}
+
+// assigned < target * n without rounding: target = m * 2^e with a 53-bit integer m, so the test is
+// assigned < ceil(m * n / 2^-e) in integers
+static bool below_target(uint64_t assigned, uint64_t n, double target)
+{
+    if (!(target > 0.0) || n == 0) return false;
+    int e;
+    const double fr = std::frexp(target, &e);
+    const unsigned __int128 m = (unsigned __int128)(uint64_t)std::ldexp(fr, 53);
+    e -= 53;
+    unsigned __int128 rhs = m * n; // below 2^117
+    if (e >= 0) return e > 10 ? true : assigned < (rhs << e);
+    const int s = -e;
+    if (s >= 127) return assigned < 1; // 0 < target * n < 1
+    const unsigned __int128 up = (rhs + (((unsigned __int128)1 << s) - 1)) >> s; // ceil(rhs / 2^s)
+    return assigned < up;
+}
+
+// Algorithm 2 on the histogram.  A class's candidates are its non-empty vote counts in ascending order
+// (descending uncertainty); slopes dI / (dC + dI) are compared exactly by cross-multiplication.
+extern "C" int sf_per_class_thresholds(const uint32_t* host_hist, uint32_t n_trees, uint32_t n_classes,
+                                       double target_fraction, uint16_t* host_vmin, double* reached_fraction)
+{
+    if (!host_hist || !host_vmin || n_trees < 1 || n_trees > 65535 || n_classes < 1 || n_classes > SF_MAX_CLASSES)
+        return SF_EINVAL;
+    const uint32_t bins = n_trees + 1u;
+    auto cell = [&](uint32_t c, uint32_t v, uint32_t wrong) -> uint64_t { return host_hist[((size_t)c * bins + v) * 2u + wrong]; };
+    uint64_t n = 0;
+    for (size_t b = 0; b < (size_t)n_classes * bins * 2u; ++b) n += host_hist[b];
+    uint32_t next[SF_MAX_CLASSES]; // first vote count of the class not yet assigned
+    for (uint32_t c = 0; c < n_classes; ++c) {
+        next[c] = 0;
+        host_vmin[c] = 0;
+    }
+    uint64_t assigned = 0;
+    while (below_target(assigned, n, target_fraction)) {
+        int best = -1;
+        uint64_t best_i = 0, best_t = 1;
+        uint32_t best_v = 0;
+        for (uint32_t c = 0; c < n_classes; ++c) {
+            uint32_t v = next[c];
+            while (v < bins && cell(c, v, 0) + cell(c, v, 1) == 0) ++v; // empty vote counts are no candidates
+            if (v >= bins) continue;
+            const uint64_t di = cell(c, v, 1), dt = cell(c, v, 0) + di;
+            // di / dt > best_i / best_t  <=>  di * best_t > best_i * dt   (counts below 2^32: no overflow)
+            if (best < 0 || di * best_t > best_i * dt) {
+                best = (int)c;
+                best_i = di;
+                best_t = dt;
+                best_v = v;
+            }
+        }
+        if (best < 0) break;
+        next[best] = best_v + 1u;
+        host_vmin[best] = (uint16_t)(best_v + 1u > 65535u ? 65535u : best_v + 1u);
+        assigned += best_t;
+    }
+    if (reached_fraction) *reached_fraction = n ? (double)assigned / (double)n : 0.0;
+    return SF_OK;
 }

@@ -142,9 +142,14 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
     }
     uint4 fb[kRing][kNI];
 #pragma unroll
-    for (int s = 0; s < kRing; ++s)
+    for (int s = 0; s < kRing; ++s) {
 #pragma unroll
         for (int j = 0; j < kNI; ++j) fb[s][j] = wl[j][s * 64 + lane];
+        // issue the ring's first loads in ring order: the counter wait in front of an MFMA is
+        // placed for the worst order on any path into the loop, and a prefill issued out of
+        // order makes every k-step wait for the newest load instead of the oldest
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // the activation operands are double-buffered too: those of k-step ks+1 are read from shared
     // memory before the MFMAs of k-step ks are issued (H has 8 columns of padding, so the read
     // one step past the end stays inside the row)

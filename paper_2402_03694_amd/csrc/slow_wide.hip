@@ -92,8 +92,10 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
 #pragma unroll
                 for (int q = 0; q < 4; ++q) acc[i][j][4 * g + q] = b[q];
         }
-    // weight operands: a column block past the end repeats the last one, its results are not stored
-    const bool wave_has_cols = nb0 < nb_total;
+    // weight operands: a column block past the end repeats the last one, its results are not stored.
+    // (A wave whose columns all lie past the end still runs the loop: a branch around the refills
+    // would make the wait in front of the slab store, which is placed for the worst path, drain the
+    // whole ring once per slab.)
     const uint4* wl[WNI];
 #pragma unroll
     for (int j = 0; j < WNI; ++j) {
@@ -102,9 +104,11 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
     }
     uint4 fb[WRING][WNI];
 #pragma unroll
-    for (int s = 0; s < WRING; ++s)
+    for (int s = 0; s < WRING; ++s) {
 #pragma unroll
         for (int j = 0; j < WNI; ++j) fb[s][j] = wl[j][s * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0); // ring order: keeps the counter waits inside the loop at "oldest load"
+    }
     __syncthreads(); // slab 0 is in place
 
     for (uint32_t sl = 0; sl < n_slabs; ++sl) {
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
                                             AMODE != A_BF16 ? s_flow[cr[u]] : 0u, (sl + 1) * WSLAB + ck);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (wave_has_cols) {
+        {
             const uint16_t* arow = slab + (sl & 1u) * (WBM * WLDS) + (lane & 31u) * WLDS + 8u * (lane >> 5);
 #pragma unroll
             for (int s = 0; s < WRING; ++s) {

@@ -15,10 +15,10 @@ header-bit features and 5-60 % escalated flows follow Sections 3.1, 4.4, 5.3.
 """
 from .configs import CONFIGS, WorkloadConfig, get_config
 from .packets import make_packets, PacketBatch
-from .models import make_forest, make_mlp, make_tree, make_gbdt, Forest, Gbdt, Mlp, Tree, round_to_bf16
+from .models import make_forest, make_mlp, make_tree, make_gbdt, make_truth, Forest, Gbdt, Mlp, Tree, round_to_bf16
 
 __all__ = [
     "CONFIGS", "WorkloadConfig", "get_config",
     "make_packets", "PacketBatch",
-    "make_forest", "make_mlp", "make_tree", "make_gbdt", "Gbdt", "Forest", "Mlp", "Tree", "round_to_bf16",
+    "make_forest", "make_mlp", "make_tree", "make_gbdt", "make_truth", "Gbdt", "Forest", "Mlp", "Tree", "round_to_bf16",
 ]

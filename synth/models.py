@@ -133,6 +133,24 @@ def make_gbdt(cfg: WorkloadConfig, feat_sample: np.ndarray, seed: Optional[int] 
     return Gbdt(T, d, C, F, node_feat, node_thr, leaf_value, base)
 
 
+def make_truth(cfg: WorkloadConfig, pred: np.ndarray, top_votes: np.ndarray, seed: Optional[int] = None) -> np.ndarray:
+    """Synthetic ground truth for a validation set (the paper's come with its datasets): the fast
+    model's label is right with a probability that rises with its confidence, at a class-dependent
+    rate, so that classes differ in how informative their uncertainty is (the situation per-class
+    thresholds are made for).  p(correct) = clip(a_c + b_c * top_votes / n_trees, 0.02, 0.98) with
+    a_c ~ U(-0.6, 0.1), b_c ~ U(3, 7); a wrong label is uniform over the other classes.
+    pred and top_votes are inputs: whoever calls this has computed them."""
+    seed = cfg.model_seed if seed is None else seed
+    rng = np.random.Generator(np.random.PCG64(seed * 1000 + 5))
+    C, T = cfg.n_classes, cfg.n_trees
+    a, b = rng.uniform(-0.6, 0.1, size=C), rng.uniform(3.0, 7.0, size=C)
+    pred = np.asarray(pred).astype(np.int64)
+    p = np.clip(a[pred] + b[pred] * np.asarray(top_votes, np.float64) / T, 0.02, 0.98)
+    right = rng.random(pred.shape[0]) < p
+    other = (pred + 1 + rng.integers(0, max(C - 1, 1), size=pred.shape[0])) % C
+    return np.where(right, pred, other).astype(np.uint16)
+
+
 def _xavier(rng, fan_out, fan_in):
     a = np.sqrt(6.0 / (fan_in + fan_out))
     return rng.uniform(-a, a, size=(fan_out, fan_in)).astype(np.float32)

@@ -74,3 +74,39 @@ def test_score_histogram_on_device(sf, T, n):
     hist = ctx.sf_score_histogram(d_top, T)
     assert hist == np.bincount(top, minlength=T + 1).tolist()
     assert ctx.sf_score_histogram(d_top[:0], T, n_flows=0) == [0] * (T + 1)
+
+
+@pytest.mark.gpu
+def test_per_class_thresholds_end_to_end(sf):
+    """Algorithm 2: class-by-score histogram on the device, slope search on the host, then the per-class
+    gate; every stage against the oracle on the same validation flows."""
+    import torch
+    import synth
+    cfg = synth.get_config(2).scaled(40000 + 9)
+    pk = synth.make_packets(cfg)
+    feat, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=8)
+    forest = synth.make_forest(cfg, feat[:4096])
+    _, pred, top, _ = oracle.fast_infer(feat, forest, want_votes=False, n_threads=8)
+    truth = synth.make_truth(cfg, pred, top)
+    n, C, T = pred.size, cfg.n_classes, cfg.n_trees
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n))
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to("cuda:0")
+    d_top, d_pred, d_truth = dev(top), dev(pred), dev(truth)
+    hist = ctx.sf_class_score_histogram(d_top, d_pred, d_truth, T, C)
+    want_h = np.zeros((C, T + 1, 2), np.int64)
+    np.add.at(want_h, (pred.astype(int), top.astype(int), (pred != truth).astype(int)), 1)
+    assert np.array_equal(np.array(hist, np.int64).reshape(C, T + 1, 2), want_h)
+    esc = torch.full((n,), -1, dtype=torch.int32, device="cuda:0")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for target in (0.05, 0.25, 0.5):
+        vmin, reached = sf.sf_per_class_thresholds(hist, T, C, target)
+        o_vmin, o_frac, _ = oracle.per_class_thresholds(pred, top, truth == pred, T, C, target)
+        assert vmin == o_vmin.tolist() and reached == o_frac
+        ctx.sf_route(d_top, d_pred, vmin, esc, cnt)
+        torch.cuda.synchronize()
+        want = oracle.route(top, pred, o_vmin)
+        k = int(cnt.cpu().numpy().view(np.uint32)[0])
+        assert k == want.size == round(reached * n)
+        assert np.array_equal(esc.cpu().numpy().view(np.uint32)[:k], want)
+    # an empty batch gives an all-zero histogram without touching the device
+    assert sum(ctx.sf_class_score_histogram(d_top, d_pred, d_truth, T, C, n_flows=0)) == 0
