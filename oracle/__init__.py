@@ -243,6 +243,48 @@ def per_class_thresholds(pred, top_votes, correct, n_trees: int, n_classes: int,
     return np.asarray(vmin, np.uint16), (assigned / n if n else 0.0), taken
 
 
+class FlowJoin:
+    """The two queues in front of the slow model (Section 3.1): queue 3 carries the flows the fast model
+    hands on, queue 2 the features of their later packets, both keyed by flow ID; the slow model takes a
+    flow when both are there; what finds no partner in the other queue is discarded after a timeout.
+
+    Batched reading: one step = (1) discard every waiting record older than ``timeout`` ticks
+    (``now - stamp > timeout``, 32-bit wrap-around arithmetic), (2) take the step's arrivals of both
+    queues, stamped ``now``; a flow ID present on both sides (waiting or just arrived) is a match: it
+    yields the pair (queue-3 value, queue-2 value) once and leaves both sides; the rest waits.  Within
+    one side a flow ID may be waiting or arriving only once (a second record is invalid input).
+    The result does not depend on the order in which records are looked at; pairs are returned sorted by
+    flow ID here (the library returns them in no particular order)."""
+
+    def __init__(self):
+        self.wait3, self.wait2 = {}, {}          # flow id -> (value, stamp)
+
+    def step(self, now, timeout, q3_id, q3_val, q2_id, q2_val):
+        now, timeout = int(now) & 0xFFFFFFFF, int(timeout)
+        expired = 0
+        for side in (self.wait3, self.wait2):
+            old = [k for k, (_, st) in side.items() if ((now - st) & 0xFFFFFFFF) > timeout]
+            for k in old:
+                del side[k]
+            expired += len(old)
+        for k, v in zip(np.asarray(q3_id, np.uint64).tolist(), np.asarray(q3_val, np.uint32).tolist()):
+            if k in self.wait3:
+                raise ValueError("flow %d twice in queue 3" % k)
+            self.wait3[k] = (v, now)
+        for k, v in zip(np.asarray(q2_id, np.uint64).tolist(), np.asarray(q2_val, np.uint32).tolist()):
+            if k in self.wait2:
+                raise ValueError("flow %d twice in queue 2" % k)
+            self.wait2[k] = (v, now)
+        both = sorted(set(self.wait3) & set(self.wait2))
+        pairs = [(k, self.wait3.pop(k)[0], self.wait2.pop(k)[0]) for k in both]
+        return pairs, expired
+
+    def pending(self, side):
+        """sorted (flow id, value, stamp) of one side (3 or 2)"""
+        d = self.wait3 if side == 3 else self.wait2
+        return sorted((k, v, st) for k, (v, st) in d.items())
+
+
 def slow_infer(esc_idx, mlp, n_flows: int, feat=None, flow_off=None, pkt_hdr=None, raw_pkts: int = 0,
                raw_bits: int = 0, labels: Optional[np.ndarray] = None, n_threads: int = 1):
     """mlp: any object with dims, dtype, w1..b3, mu, inv_sigma, clamp.  Returns (logits, labels);
