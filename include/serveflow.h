@@ -283,6 +283,46 @@ int sf_route_score(sf_ctx* ctx, const float* score, uint32_t n_flows, float thre
 int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_flows, const double* host_q, uint32_t n_q,
                        float* host_thresholds);
 
+/* ---- the two queues in front of the slow model ----------------------------------------------
+ * Section 3.1: the flows the fast model hands on go to queue 3; the features of their later
+ * packets accumulate, with their flow IDs, in queue 2; the slow model combines the two by flow
+ * ID; records without a partner in the other queue are discarded after a timeout.
+ *
+ * Here both queues are hash tables in device memory, keyed by a 64-bit flow ID (any value but
+ * 0 and 2^64-1), each record carrying a 32-bit value (for queue 3 typically the flow's row in
+ * the label array, for queue 2 the row of its late-packet features) and the tick it arrived at.
+ * One call is one step:
+ *   1. every waiting record with now - stamp > timeout (32-bit wrap-around) is discarded;
+ *   2. the arrivals of both queues are taken, stamped now; a flow ID present on both sides
+ *      (waiting or just arrived) yields one pair (queue-3 value, queue-2 value) and leaves both
+ *      tables; the rest waits.
+ * The outcome does not depend on the order of the arrivals.  A flow ID may wait or arrive only
+ * once per side; a second record of a side is dropped and counted.
+ *
+ * table: caller-owned device memory of sf_join_table_bytes(cap_log2) bytes, 16-byte aligned,
+ * zero-filled before its first use, holding 2^cap_log2 slots per side (keep each side at most
+ * half full).  The workspace of the context must have sf_join_workspace_bytes(cap_log2) bytes.
+ * pair_q3 / pair_q2: [pair_cap], pair k = (pair_q3[k], pair_q2[k]) in no particular order;
+ * *n_pairs (device) = number of pairs found (pairs beyond pair_cap are lost and counted).
+ * stats: optional device array of 4 words: discarded after the timeout, arrivals that found
+ * no free slot, arrivals whose flow ID was already on their side, pairs beyond pair_cap. */
+typedef struct {
+    void* slots;       /* device */
+    uint32_t cap_log2; /* 4..28 */
+} sf_join_table;
+
+size_t sf_join_table_bytes(uint32_t cap_log2);
+size_t sf_join_workspace_bytes(uint32_t cap_log2);
+int sf_join_step(sf_ctx* ctx, const sf_join_table* table, uint32_t now, uint32_t timeout,
+                 const uint64_t* q3_id, const uint32_t* q3_val, uint32_t n3,
+                 const uint64_t* q2_id, const uint32_t* q2_val, uint32_t n2,
+                 uint32_t* pair_q3, uint32_t* pair_q2, uint32_t pair_cap, uint32_t* n_pairs, uint32_t* stats);
+
+/* The records waiting in one queue (queue = 3 or 2), in no particular order: ids, vals, stamps:
+ * device arrays of cap entries (vals and stamps optional); *count (device) = number waiting. */
+int sf_join_pending(sf_ctx* ctx, const sf_join_table* table, int queue, uint64_t* ids, uint32_t* vals,
+                    uint32_t* stamps, uint32_t cap, uint32_t* count);
+
 /* ---- step 5: slow model on the escalated flows only ------------------------------------
  * Sections 3.1 and 4.4: only flows the fast model is unsure of reach the slow model, and
  * its answer replaces the fast one.  The slow model is a 3-layer ReLU MLP.

@@ -23,7 +23,8 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_vmin_from_theta", "sf_slow_infer", "sf_score_histogram", "sf_universal_thresholds",
            "sf_vmin_for_target", "sf_fastest_infer", "sf_validate_tree", "sf_route_ratio",
            "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
-           "sf_class_score_histogram", "sf_per_class_thresholds")
+           "sf_class_score_histogram", "sf_per_class_thresholds", "sf_join_table_bytes", "sf_join_workspace_bytes",
+           "sf_join_step", "sf_join_pending")
 
 
 class SfPackets(ctypes.Structure):
@@ -54,6 +55,10 @@ class SfGbdt(ctypes.Structure):
     _fields_ = [("n_trees", ctypes.c_uint32), ("depth", ctypes.c_uint32), ("n_classes", ctypes.c_uint32),
                 ("n_features", ctypes.c_uint32), ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p),
                 ("leaf_value", ctypes.c_void_p), ("base", ctypes.c_void_p)]
+
+
+class SfJoinTable(ctypes.Structure):
+    _fields_ = [("slots", ctypes.c_void_p), ("cap_log2", ctypes.c_uint32)]
 
 
 SF_SCORE_LC, SF_SCORE_ENTROPY = 0, 1
@@ -117,6 +122,14 @@ def load_library() -> ctypes.CDLL:
     lib.sf_per_class_thresholds.restype = ctypes.c_int
     lib.sf_per_class_thresholds.argtypes = [ctypes.POINTER(ctypes.c_uint32), u32, u32, ctypes.c_double,
                                             ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_double)]
+    lib.sf_join_table_bytes.restype = sz
+    lib.sf_join_table_bytes.argtypes = [u32]
+    lib.sf_join_workspace_bytes.restype = sz
+    lib.sf_join_workspace_bytes.argtypes = [u32]
+    lib.sf_join_step.restype = ctypes.c_int
+    lib.sf_join_step.argtypes = [vp, ctypes.POINTER(SfJoinTable), u32, u32, vp, vp, u32, vp, vp, u32, vp, vp, u32, vp, vp]
+    lib.sf_join_pending.restype = ctypes.c_int
+    lib.sf_join_pending.argtypes = [vp, ctypes.POINTER(SfJoinTable), ctypes.c_int, vp, vp, vp, u32, vp]
     lib.sf_gbdt_infer.restype = ctypes.c_int
     lib.sf_gbdt_infer.argtypes = [vp, vp, u32, u32, ctypes.POINTER(SfGbdt), ctypes.c_int, vp, vp, vp, vp]
     lib.sf_route_score.restype = ctypes.c_int
@@ -175,6 +188,27 @@ def sf_universal_thresholds(hist, n_trees: int, quantiles):
     if rc != SF_OK:
         raise ServeFlowError(rc, "sf_universal_thresholds: bad arguments or empty histogram")
     return list(out)
+
+
+def sf_join_table_bytes(cap_log2: int) -> int:
+    return int(lib().sf_join_table_bytes(cap_log2))
+
+
+def sf_join_workspace_bytes(cap_log2: int) -> int:
+    return int(lib().sf_join_workspace_bytes(cap_log2))
+
+
+class DeviceJoinTable:
+    """Both queues' hash tables in one zero-filled device buffer."""
+
+    def __init__(self, cap_log2: int, device="cuda:0"):
+        self.cap_log2 = cap_log2
+        self.buf = torch.zeros(sf_join_table_bytes(cap_log2) // 8, dtype=torch.int64, device=device)
+
+    def c_struct(self) -> SfJoinTable:
+        t = SfJoinTable()
+        t.slots, t.cap_log2 = self.buf.data_ptr(), self.cap_log2
+        return t
 
 
 def sf_per_class_thresholds(hist, n_trees: int, n_classes: int, target: float):
@@ -402,6 +436,26 @@ class ServeFlow:
         self._check(self._lib.sf_route_subset(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16),
                                               _ptr(idx, torch.int32), _ptr(idx_count, torch.int32), cap, arr, len(vm),
                                               _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    # ---- the queues in front of the slow model -----------------------------------------------
+    def sf_join_step(self, table: "DeviceJoinTable", now: int, timeout: int, q3_id, q3_val, q2_id, q2_val,
+                     pair_q3: torch.Tensor, pair_q2: torch.Tensor, n_pairs: torch.Tensor,
+                     stats: Optional[torch.Tensor] = None):
+        t = table.c_struct()
+        n3 = 0 if q3_id is None else int(q3_id.shape[0])
+        n2 = 0 if q2_id is None else int(q2_id.shape[0])
+        self._check(self._lib.sf_join_step(
+            self._h, ctypes.byref(t), int(now) & 0xFFFFFFFF, int(timeout), _ptr(q3_id, torch.int64) if n3 else None,
+            _ptr(q3_val, torch.int32) if n3 else None, n3, _ptr(q2_id, torch.int64) if n2 else None,
+            _ptr(q2_val, torch.int32) if n2 else None, n2, _ptr(pair_q3, torch.int32), _ptr(pair_q2, torch.int32),
+            int(pair_q3.shape[0]), _ptr(n_pairs, torch.int32), _ptr(stats, torch.int32)))
+
+    def sf_join_pending(self, table: "DeviceJoinTable", queue: int, ids: torch.Tensor, vals: Optional[torch.Tensor],
+                        stamps: Optional[torch.Tensor], count: torch.Tensor):
+        t = table.c_struct()
+        self._check(self._lib.sf_join_pending(self._h, ctypes.byref(t), int(queue), _ptr(ids, torch.int64),
+                                              _ptr(vals, torch.int32), _ptr(stamps, torch.int32), int(ids.shape[0]),
+                                              _ptr(count, torch.int32)))
 
     # ---- boosted trees as the fast model, real-valued scores --------------------------------
     def sf_gbdt_infer(self, feat: torch.Tensor, model: DeviceGbdt, score_kind: int, pred: torch.Tensor,

@@ -48,6 +48,7 @@ def test_struct_layouts_match_header(tmp_path):
               "sf_tree": (b.SfTree, ["depth", "n_classes", "n_features", "node_feat", "node_thr", "leaf_count"]),
               "sf_gbdt": (b.SfGbdt, ["n_trees", "depth", "n_classes", "n_features", "node_feat", "node_thr",
                                      "leaf_value", "base"]),
+              "sf_join_table": (b.SfJoinTable, ["slots", "cap_log2"]),
               "sf_mlp": (b.SfMlp, ["n_in", "n_h1", "n_h2", "n_classes", "dtype", "mu", "inv_sigma", "clamp",
                                    "w1", "w2", "w3", "b1", "b2", "b3"])}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "serveflow.h"', 'int main(void){']
