@@ -358,6 +358,16 @@ int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_pac
                   const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_flows,
                   const sf_mlp* mlp, const uint16_t* pred, float* logits, uint16_t* labels);
 
+/* The slow model behind the queue join (Section 3.1: it combines the features of the later
+ * packets with the flow handed on by the fast model): pair k reads row pair_row[k] of feat
+ * ([n_rows][feat_ld], e.g. the late-packet features; entries >= n_rows are clamped) and writes
+ * its label to labels[pair_flow[k]] ([n_flows]; entries >= n_flows are skipped).  pair_row,
+ * pair_flow, n_pairs: device, as written by sf_join_step (its pair_q2, pair_q3, n_pairs); at
+ * most pair_cap pairs are processed.  logits: optional [pair_cap][n_classes], row k = pair k. */
+int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows,
+                        const uint32_t* pair_row, const uint32_t* pair_flow, const uint32_t* n_pairs,
+                        uint32_t pair_cap, uint32_t n_flows, const sf_mlp* mlp, float* logits, uint16_t* labels);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_vmin_for_target", "sf_fastest_infer", "sf_validate_tree", "sf_route_ratio",
            "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
            "sf_class_score_histogram", "sf_per_class_thresholds", "sf_join_table_bytes", "sf_join_workspace_bytes",
-           "sf_join_step", "sf_join_pending")
+           "sf_join_step", "sf_join_pending", "sf_slow_infer_pairs")
 
 
 class SfPackets(ctypes.Structure):
@@ -122,6 +122,8 @@ def load_library() -> ctypes.CDLL:
     lib.sf_per_class_thresholds.restype = ctypes.c_int
     lib.sf_per_class_thresholds.argtypes = [ctypes.POINTER(ctypes.c_uint32), u32, u32, ctypes.c_double,
                                             ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_double)]
+    lib.sf_slow_infer_pairs.restype = ctypes.c_int
+    lib.sf_slow_infer_pairs.argtypes = [vp, vp, u32, u32, vp, vp, vp, u32, u32, ctypes.POINTER(SfMlp), vp, vp]
     lib.sf_join_table_bytes.restype = sz
     lib.sf_join_table_bytes.argtypes = [u32]
     lib.sf_join_workspace_bytes.restype = sz
@@ -436,6 +438,18 @@ class ServeFlow:
         self._check(self._lib.sf_route_subset(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16),
                                               _ptr(idx, torch.int32), _ptr(idx_count, torch.int32), cap, arr, len(vm),
                                               _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_slow_infer_pairs(self, mlp: DeviceMlp, feat: torch.Tensor, pair_row: torch.Tensor, pair_flow: torch.Tensor,
+                            n_pairs: torch.Tensor, labels: torch.Tensor, logits: Optional[torch.Tensor] = None,
+                            pair_cap: Optional[int] = None):
+        m = mlp.c_struct()
+        cap = int(pair_row.shape[0]) if pair_cap is None else int(pair_cap)
+        if logits is not None:
+            cap = min(cap, int(logits.shape[0]))
+        self._check(self._lib.sf_slow_infer_pairs(
+            self._h, _ptr(feat, torch.float32), int(feat.shape[1]), int(feat.shape[0]), _ptr(pair_row, torch.int32),
+            _ptr(pair_flow, torch.int32), _ptr(n_pairs, torch.int32), cap, int(labels.shape[0]), ctypes.byref(m),
+            _ptr(logits, torch.float32), _ptr(labels, torch.int16)))
 
     # ---- the queues in front of the slow model -----------------------------------------------
     def sf_join_step(self, table: "DeviceJoinTable", now: int, timeout: int, q3_id, q3_val, q2_id, q2_val,

@@ -19,10 +19,13 @@ enum { A_BF16 = 0, A_FEAT = 1, A_RAW = 2 };
 
 struct LayerArgs {
     // rows
-    const uint32_t* esc_idx;
+    const uint32_t* esc_idx;  // row e reads the input row esc_idx[e] (clamped below n_rows) ...
+    const uint32_t* scatter;  // ... and its label goes to labels[scatter[e]]; NULL = the same index
     const uint32_t* esc_count;
     uint32_t esc_cap;
     uint32_t row_begin; // first escalated row of this chunk
+    uint32_t n_rows;    // rows of the input (feature matrix or flows of the packet arrays)
+    uint32_t n_labels;  // entries of labels; a label index outside is not written
     // A operand
     const uint16_t* a_bf16; // [rows_in_chunk][lda]
     uint32_t lda;

@@ -9,8 +9,9 @@
 // consecutive rows fall on distinct banks); the weights are re-ordered once per call so that
 // the 8 K-values a lane needs for an MFMA B operand are contiguous and a wave's operand is one
 // contiguous kilobyte, and are then read straight from the cache into registers.  There is no
-// barrier inside a layer's K loop.  The last layer (at most 32 classes) is one 32x32 block for
-// each of four waves, followed by a per-row arg-max in registers and the scatter of the label.
+// barrier inside a layer's K loop.  The last layer (at most 32 classes) runs on all eight waves
+// (four row blocks x two halves of K), followed by a per-row arg-max in registers and the
+// scatter of the label.
 // Blocks are persistent: each walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... up to the
 // device-side escalation count, so no block is launched for rows that do not exist.
 #include "mlp_common.h"
@@ -18,8 +19,9 @@
 namespace sf {
 bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
 size_t slow_fused_ws_bytes(const sf_mlp* mlp);
-int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
-               const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* mlp, float* logits, uint16_t* labels);
+int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint32_t n_rows, const uint32_t* esc_idx,
+               const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_labels, const sf_mlp* mlp,
+               float* logits, uint16_t* labels);
 } // namespace sf
 
 namespace {
@@ -35,9 +37,11 @@ constexpr uint32_t kPadK = 64; // every K is padded to this (four k-steps of 16)
 __host__ __device__ inline uint32_t up(uint32_t x, uint32_t m) { return (x + m - 1u) / m * m; }
 
 struct FusedArgs {
-    const uint32_t* esc_idx;
+    const uint32_t* esc_idx;  // row e reads feature row esc_idx[e] (clamped below n_rows) ...
+    const uint32_t* scatter;  // ... and its label goes to labels[scatter[e]]; NULL = the same index
     const uint32_t* esc_count;
     uint32_t esc_cap;
+    uint32_t n_rows, n_labels;
     const float* feat;
     uint32_t feat_ld;
     const float* mu;
@@ -226,6 +230,8 @@ __device__ __forceinline__ void bias_acc(f32x16 (&acc)[kMI][kNI], const float* s
 }
 
 constexpr uint32_t kNoFlow = 0xFFFFFFFFu;
+// a bad list entry must not leave the feature matrix
+__device__ __forceinline__ uint32_t clamp_row(uint32_t f, uint32_t n_rows) { return f < n_rows ? f : n_rows - 1u; }
 constexpr int kXr = 2; // 8-value input chunks a thread can hold in registers for the next tile
 
 // raw feature values [k, k+8) of one flow (zeros for a missing flow or past n_in)
@@ -311,7 +317,7 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
     {
         // first tile: flow ids and feature rows are fetched here, with nothing to overlap them
         const uint32_t tid = threadIdx.x, row0 = blockIdx.x * FBM;
-        if (tid < FBM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : kNoFlow;
+        if (tid < FBM) s_flow[tid] = row0 + tid < total ? clamp_row(a.esc_idx[row0 + tid], a.n_rows) : kNoFlow;
         __syncthreads();
         if (in_regs) {
 #pragma unroll
@@ -335,7 +341,7 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
         uint32_t* flow_next = s_flow + (cur ^ 1u) * FBM;
         // flow ids of the next tile: requested now, parked in shared memory after layer 1
         uint32_t nf = kNoFlow;
-        if (has_next && tid < FBM && next_row0 + tid < total) nf = a.esc_idx[next_row0 + tid];
+        if (has_next && tid < FBM && next_row0 + tid < total) nf = clamp_row(a.esc_idx[next_row0 + tid], a.n_rows);
         // input tile of this tile (H is free: the previous tile's last layer ended with a barrier)
         if (in_regs) {
 #pragma unroll
@@ -437,7 +443,10 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
                 const float ov = __shfl_xor(bv, 32, 64);
                 const uint32_t ob = (uint32_t)__shfl_xor((int)best, 32, 64);
                 if (ob != kNoFlow && (best == kNoFlow || ov > bv || (ov == bv && ob < best))) best = ob;
-                if (lane < 32u && row_ok) a.labels[flow_cur[r]] = (uint16_t)best;
+                if (lane < 32u && row_ok) {
+                    const uint32_t dst = a.scatter ? a.scatter[row0 + r] : flow_cur[r];
+                    if (dst < a.n_labels) a.labels[dst] = (uint16_t)best;
+                }
             }
         }
         cur ^= 1u;
@@ -489,8 +498,9 @@ int reorder_weights_async(sf_ctx* ctx, const ReorderSpec* specs, int n_specs)
     return SF_OK;
 }
 
-int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
-               const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* m, float* logits, uint16_t* labels)
+int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint32_t n_rows, const uint32_t* esc_idx,
+               const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_labels, const sf_mlp* m,
+               float* logits, uint16_t* labels)
 {
     char* p = (char*)ws;
     uint4* w1s = (uint4*)p;
@@ -506,8 +516,11 @@ int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const
     }
     FusedArgs a;
     a.esc_idx = esc_idx;
+    a.scatter = scatter;
     a.esc_count = esc_count;
     a.esc_cap = esc_cap;
+    a.n_rows = n_rows;
+    a.n_labels = n_labels;
     a.feat = feat;
     a.feat_ld = feat_ld;
     a.mu = m->mu;

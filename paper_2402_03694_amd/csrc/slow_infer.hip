@@ -17,8 +17,9 @@ namespace sf {
 // fused single-kernel form for narrow hidden layers (slow_fused.hip)
 bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
 size_t slow_fused_ws_bytes(const sf_mlp* mlp);
-int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, const uint32_t* esc_idx,
-               const uint32_t* esc_count, uint32_t esc_cap, const sf_mlp* mlp, float* logits, uint16_t* labels);
+int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint32_t n_rows, const uint32_t* esc_idx,
+               const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_labels, const sf_mlp* mlp,
+               float* logits, uint16_t* labels);
 // one hidden layer of any width on operand-ordered weights (slow_wide.hip)
 int wide_layer(sf_ctx* ctx, int amode, const sfmlp::LayerArgs& a, const void* w_ordered, uint32_t rows_cap);
 } // namespace sf
@@ -54,7 +55,12 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
     const uint32_t col0 = blockIdx.y * BN;
 
     if (AMODE != A_BF16 || FINAL) {
-        if (tid < BM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : 0u;
+        if (tid < BM) {
+            // FINAL: the index the label goes to; otherwise the input row (clamped into the input)
+            uint32_t f = 0u;
+            if (row0 + tid < total) f = (FINAL && a.scatter) ? a.scatter[row0 + tid] : a.esc_idx[row0 + tid];
+            s_flow[tid] = (FINAL || f < a.n_rows) ? f : a.n_rows - 1u;
+        }
         __syncthreads();
     }
 
@@ -157,7 +163,7 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
                     best = c;
                 }
             }
-            a.labels[s_flow[tid]] = (uint16_t)best;
+            if (s_flow[tid] < a.n_labels) a.labels[s_flow[tid]] = (uint16_t)best;
         }
     }
 }
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
 struct F32Args {
     const uint32_t* esc_idx;
     const uint32_t* esc_count;
-    uint32_t esc_cap, row_begin, rows_cap;
+    uint32_t esc_cap, row_begin, rows_cap, n_rows;
     const float* feat;
     uint32_t feat_ld;
     const float* mu;
@@ -189,7 +195,8 @@ __global__ __launch_bounds__(256) void f32_input(F32Args a, float* __restrict__ 
     const uint64_t n = (uint64_t)rows * a.n_in;
     for (uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n; g += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t r = (uint32_t)(g / a.n_in), k = (uint32_t)(g % a.n_in);
-        const uint32_t flow = a.esc_idx[a.row_begin + r];
+        uint32_t flow = a.esc_idx[a.row_begin + r];
+        flow = flow < a.n_rows ? flow : a.n_rows - 1u; // a bad list entry must not leave the input
         float v;
         if (a.feat) {
             v = a.feat[(size_t)flow * a.feat_ld + k];
@@ -239,9 +246,10 @@ __global__ __launch_bounds__(256) void f32_layer(const uint32_t* esc_count, uint
     }
 }
 
-__global__ __launch_bounds__(256) void f32_argmax(const uint32_t* esc_idx, const uint32_t* esc_count, uint32_t esc_cap,
+__global__ __launch_bounds__(256) void f32_argmax(const uint32_t* label_idx, const uint32_t* esc_count, uint32_t esc_cap,
                                                   uint32_t row_begin, uint32_t rows_cap, const float* __restrict__ lg,
-                                                  uint32_t C, float* __restrict__ logits, uint16_t* __restrict__ labels)
+                                                  uint32_t C, float* __restrict__ logits, uint16_t* __restrict__ labels,
+                                                  uint32_t n_labels)
 {
     uint32_t total = *esc_count;
     total = total < esc_cap ? total : esc_cap;
@@ -260,7 +268,8 @@ __global__ __launch_bounds__(256) void f32_argmax(const uint32_t* esc_idx, const
                 best = c;
             }
         }
-        labels[esc_idx[row_begin + r]] = (uint16_t)best;
+        const uint32_t dst = label_idx[row_begin + r];
+        if (dst < n_labels) labels[dst] = (uint16_t)best;
     }
 }
 
@@ -288,12 +297,14 @@ uint32_t pad64(uint32_t x) { return (x + 63u) / 64u * 64u; }
 
 } // namespace
 
-extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_packets* raw_src,
-                             const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx, const uint32_t* esc_count,
-                             uint32_t esc_cap, uint32_t n_flows, const sf_mlp* mlp, const uint16_t* pred, float* logits,
-                             uint16_t* labels)
+namespace {
+
+// Both entry points.  esc_idx: input rows (of feat, n_rows of them, or flows of raw_src); scatter: where the
+// labels go (NULL = esc_idx); n_flows: entries of labels.
+int run_slow(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows, const sf_packets* raw_src,
+             const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx, const uint32_t* scatter, const uint32_t* esc_count,
+             uint32_t esc_cap, uint32_t n_flows, const sf_mlp* mlp, const uint16_t* pred, float* logits, uint16_t* labels)
 {
-    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_slow_infer: ctx is NULL");
     if (!mlp) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: mlp is NULL");
     if (mlp->dtype != SF_F32 && mlp->dtype != SF_BF16) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: unknown dtype %d", mlp->dtype);
     if (!mlp->n_in || !mlp->n_h1 || !mlp->n_h2 || !mlp->n_classes)
@@ -304,7 +315,7 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: weights or biases missing");
     if ((mlp->mu == nullptr) != (mlp->inv_sigma == nullptr))
         return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: mu and inv_sigma come together");
-    if (n_flows == 0 || esc_cap == 0) return SF_OK;
+    if (n_flows == 0 || esc_cap == 0 || n_rows == 0) return SF_OK;
     if ((feat == nullptr) == (raw_src == nullptr))
         return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: give exactly one of feat and raw_src");
     if (feat && mlp->n_in > feat_ld) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: n_in %u > feat_ld %u", mlp->n_in, feat_ld);
@@ -318,7 +329,7 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         if (raw_src->n_pkts >> 32) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: n_pkts exceeds 32-bit offsets");
     }
     if (!esc_idx || !esc_count || !labels) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: esc_idx, esc_count or labels is NULL");
-    if (esc_cap > n_flows) esc_cap = n_flows;
+    if (!scatter && esc_cap > n_flows) esc_cap = n_flows;
     if (pred && pred != labels) {
         uint32_t blocks = (n_flows + 2047) / 2048;
         copy_labels<<<blocks, 256, 0, ctx->stream>>>(pred, labels, n_flows);
@@ -330,7 +341,7 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         const size_t need = sf::slow_fused_ws_bytes(mlp);
         void* w = ws.take(need);
         if (!w) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace too small for %zu bytes of re-ordered weights", need);
-        return sf::slow_fused(ctx, w, feat, feat_ld, esc_idx, esc_count, esc_cap, mlp, logits, labels);
+        return sf::slow_fused(ctx, w, feat, feat_ld, n_rows, esc_idx, scatter, esc_count, esc_cap, n_flows, mlp, logits, labels);
     }
     const bool bf = mlp->dtype == SF_BF16;
     void *w1o = nullptr, *w2o = nullptr;
@@ -360,9 +371,12 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         for (uint32_t begin = 0; begin < esc_cap; begin += R) {
             LayerArgs a = {};
             a.esc_idx = esc_idx;
+            a.scatter = scatter;
             a.esc_count = esc_count;
             a.esc_cap = esc_cap;
             a.row_begin = begin;
+            a.n_rows = n_rows;
+            a.n_labels = n_flows;
             a.labels = labels;
             // layer 1
             a.feat = feat;
@@ -429,6 +443,7 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         f.esc_cap = esc_cap;
         f.row_begin = begin;
         f.rows_cap = R;
+        f.n_rows = n_rows;
         f.feat = feat;
         f.feat_ld = feat_ld;
         f.mu = mlp->mu;
@@ -455,8 +470,32 @@ extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, c
         f32_layer<<<blocks((uint64_t)R * mlp->n_classes), 256, 0, ctx->stream>>>(
             esc_count, esc_cap, begin, R, h2, mlp->n_h2, (const float*)mlp->w3, mlp->b3, mlp->n_classes, lg, 0);
         SF_LAUNCH_CHECK(ctx, "f32_layer 3");
-        f32_argmax<<<blocks(R), 256, 0, ctx->stream>>>(esc_idx, esc_count, esc_cap, begin, R, lg, mlp->n_classes, logits, labels);
+        f32_argmax<<<blocks(R), 256, 0, ctx->stream>>>(scatter ? scatter : esc_idx, esc_count, esc_cap, begin, R, lg,
+                                                       mlp->n_classes, logits, labels, n_flows);
         SF_LAUNCH_CHECK(ctx, "f32_argmax");
     }
     return SF_OK;
+}
+
+} // namespace
+
+extern "C" int sf_slow_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, const sf_packets* raw_src,
+                             const sf_feat_cfg* raw_cfg, const uint32_t* esc_idx, const uint32_t* esc_count,
+                             uint32_t esc_cap, uint32_t n_flows, const sf_mlp* mlp, const uint16_t* pred, float* logits,
+                             uint16_t* labels)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_slow_infer: ctx is NULL");
+    return run_slow(ctx, feat, feat_ld, n_flows, raw_src, raw_cfg, esc_idx, nullptr, esc_count, esc_cap, n_flows, mlp, pred,
+                    logits, labels);
+}
+
+extern "C" int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows,
+                                   const uint32_t* pair_row, const uint32_t* pair_flow, const uint32_t* n_pairs,
+                                   uint32_t pair_cap, uint32_t n_flows, const sf_mlp* mlp, float* logits, uint16_t* labels)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_slow_infer_pairs: ctx is NULL");
+    if (!feat) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer_pairs: feat is NULL");
+    if (pair_cap && n_flows && n_rows && !pair_flow) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer_pairs: pair_flow is NULL");
+    return run_slow(ctx, feat, feat_ld, n_rows, nullptr, nullptr, pair_row, pair_flow, n_pairs, pair_cap, n_flows, mlp,
+                    nullptr, logits, labels);
 }

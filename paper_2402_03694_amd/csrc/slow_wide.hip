@@ -64,7 +64,10 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
     const uint32_t nb0 = col0 / 32u + wave * WNI;
 
     if (AMODE != A_BF16) {
-        if (tid < WBM) s_flow[tid] = row0 + tid < total ? a.esc_idx[row0 + tid] : 0u;
+        if (tid < WBM) {
+            uint32_t f = row0 + tid < total ? a.esc_idx[row0 + tid] : 0u;
+            s_flow[tid] = f < a.n_rows ? f : a.n_rows - 1u; // a bad list entry must not leave the input
+        }
         __syncthreads();
     }
     // two 16-byte chunks of the slab per thread: rows r, 8 k-values each
