@@ -193,6 +193,75 @@ def three_tier(args, cfg):
     print(json.dumps(out))
 
 
+def join_bench(args):
+    """--join: the queue join in front of the slow model at config 2's rates: per step 179,427 flows are handed
+    on (queue 3) and as many late-feature records arrive (queue 2); 70 % of a flow's two records arrive in the
+    same step, 20 % one step apart, 10 % never (and are discarded after the timeout)."""
+    import torch
+    import paper_2402_03694_amd as sf
+    dev = "cuda:0"
+    per_step, cap_log2, timeout = 179427, 20, 3
+    steps = args.steps + args.warmup
+    rng = np.random.default_rng(7)
+    n = per_step * steps
+    ids = rng.permutation(np.arange(1, n + 1, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15))   # distinct, well spread
+    t3 = np.repeat(np.arange(steps), per_step)
+    u = rng.random(n)
+    t2 = np.where(u < 0.7, t3, np.where(u < 0.8, t3 + 1, np.where(u < 0.9, t3 - 1, -1)))
+    t2 = np.where((t2 < 0) | (t2 >= steps), -1, t2)
+    ctx = sf.ServeFlow(sf.sf_join_workspace_bytes(cap_log2))
+    table = sf.DeviceJoinTable(cap_log2, dev)
+    t64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.uint64).view(np.int64)).to(dev)
+    t32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.uint32).view(np.int32)).to(dev)
+    batches = []
+    for s_ in range(steps):
+        a, b = np.flatnonzero(t3 == s_), np.flatnonzero(t2 == s_)
+        batches.append((t64(ids[a]), t32(a % (1 << 20)), t64(ids[b]), t32(b % (1 << 20)), a.size + b.size))
+    p3 = torch.empty(2 * per_step, dtype=torch.int32, device=dev)
+    p2 = torch.empty(2 * per_step, dtype=torch.int32, device=dev)
+    k = torch.zeros(1, dtype=torch.int32, device=dev)
+    stats = torch.zeros(4, dtype=torch.int32, device=dev)
+    for s_ in range(args.warmup):
+        b = batches[s_]
+        ctx.sf_join_step(table, s_, timeout, b[0], b[1], b[2], b[3], p3, p2, k, stats)
+    torch.cuda.synchronize()
+    records = 0
+    t0 = time.perf_counter()
+    for s_ in range(args.warmup, steps):
+        b = batches[s_]
+        ctx.sf_join_step(table, s_, timeout, b[0], b[1], b[2], b[3], p3, p2, k, stats)
+        records += b[4]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / args.steps
+    # per step the method must read every arrival (12 B) and write the pairs (8 B each); the tables are state
+    pairs_last = int(k.cpu().numpy().view(np.uint32)[0])
+    alg = 12.0 * records / args.steps + 8.0 * pairs_last
+    table_bytes = 3.0 * sf.sf_join_table_bytes(cap_log2)        # scan, clear, plus the survivors' round trip (bound)
+    out = {"metric": "records/sec through the queue join", "value": records / (t1 - t0), "unit": "records/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u64 keys, u32 values", "data": "synthetic",
+           "config": {"workload": "queue join: %d + ~%d arrivals per step, 2^%d slots per side, timeout %d steps"
+                                  % (per_step, per_step * 9 // 10, cap_log2, timeout), "pairs_last_step": pairs_last},
+           "roofline": {"bound": "hbm", "achieved": alg / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "kernel": "sf_join_step",
+                        "table_sweep_bytes": table_bytes}}
+    if not args.no_cpu_baseline:
+        import oracle
+        j = oracle.FlowJoin()
+        sample_steps = min(steps, 4)
+        c0 = time.perf_counter()
+        done = 0
+        for s_ in range(sample_steps):
+            a, b = np.flatnonzero(t3 == s_), np.flatnonzero(t2 == s_)
+            j.step(s_, timeout, ids[a], a, ids[b], b)
+            done += a.size + b.size
+        dt = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": done / dt, "unit": "records/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d steps of the same stream, %.1f s wall" % (sample_steps, dt)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -203,6 +272,7 @@ def main():
     ap.add_argument("--target", type=float, default=-1.0, help="override the escalated-fraction target")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0)
+    ap.add_argument("--join", action="store_true", help="time the queue join in front of the slow model instead")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -220,6 +290,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
 
+    if args.join:
+        return join_bench(args)
     cfg = synth.get_config(args.config)
     if cfg.tree0_depth:
         return three_tier(args, cfg)

@@ -43,11 +43,32 @@ __device__ __forceinline__ uint32_t slot_of(unsigned long long id, uint32_t mask
     return (uint32_t)id & mask;
 }
 
+// One atomic per wave instead of one per lane: the lanes for which want is set get consecutive positions
+// base .. base + count - 1 (base from a single atomicAdd by the first of them).  All lanes that are active at
+// the call take part; the result is meaningful only where want is set.
+__device__ __forceinline__ uint32_t wave_claim(uint32_t* counter, bool want)
+{
+    const unsigned long long m = __ballot(want);
+    if (m == 0) return 0;
+    const uint32_t lane = threadIdx.x & 63u;
+    const int leader = __ffsll((long long)m) - 1;
+    uint32_t base = 0;
+    if ((int)lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = (uint32_t)__shfl((int)base, leader, 64);
+    return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
+
+__device__ __forceinline__ void wave_count(uint32_t* counter, bool want)
+{
+    const unsigned long long m = __ballot(want);
+    if (m && (int)(threadIdx.x & 63u) == __ffsll((long long)m) - 1) atomicAdd(counter, (uint32_t)__popcll(m));
+}
+
 struct JoinArgs {
     Slot* table[2]; // [0] queue 3, [1] queue 2
     uint32_t mask;  // slots per table - 1
     uint32_t now, timeout;
-    Slot* list;     // scratch: survivors of both sides, side in bit 31 of... kept in two ranges
+    Slot* list;     // scratch: survivors, side s in list[s * slots ...]
     uint32_t* counters; // scratch: [0] survivors of side 0, [1] survivors of side 1
     uint32_t* n_pairs;
     uint32_t* pair_q3;
@@ -63,24 +84,58 @@ __global__ void join_zero(uint32_t* counters, uint32_t* n_pairs, uint32_t* stats
     if (stats && threadIdx.x >= 4 && threadIdx.x < 8) stats[threadIdx.x - 4] = 0;
 }
 
-// survivors of both tables -> list (side s occupies list[s * slots ...]); every slot is cleared
+// survivors of both tables -> list (side s occupies list[s * slots ...]); every slot is cleared.
+// A wave takes kChunk consecutive slots of one side per trip and claims the list positions of all its
+// survivors with ONE atomic (a counter that every wave of the grid adds to is the bottleneck otherwise:
+// same-address atomics retire a few nanoseconds apart).
+constexpr uint32_t kChunkTrips = 16;             // slots per lane per trip
+constexpr uint32_t kChunk = 64u * kChunkTrips;   // slots per wave per trip
+
 __global__ __launch_bounds__(256) void join_collect(JoinArgs a)
 {
     const uint32_t slots = a.mask + 1u;
-    for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < 2u * slots; g += gridDim.x * blockDim.x) {
-        const uint32_t side = g >= slots ? 1u : 0u;
-        Slot* s = a.table[side] + (g - side * slots);
-        const Slot v = *s;
-        if (v.id != kEmpty) {
-            if (v.id != kGone) {
-                if (a.now - v.stamp > a.timeout) { // unsigned: wraps like the tick counter
-                    if (a.stats) atomicAdd(&a.stats[kExpired], 1u);
-                } else {
-                    const uint32_t at = atomicAdd(&a.counters[side], 1u);
-                    a.list[(size_t)side * slots + at] = v;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, n_waves = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t chunks_per_side = (slots + kChunk - 1u) / kChunk;
+    for (uint32_t c = wave; c < 2u * chunks_per_side; c += n_waves) {
+        const uint32_t side = c >= chunks_per_side ? 1u : 0u;
+        const uint32_t first = (c - side * chunks_per_side) * kChunk;
+        Slot* t = a.table[side];
+        // pass 1: who survives (one 64-bit lane mask per trip, the same in every lane)
+        unsigned long long keep[kChunkTrips];
+        uint32_t n_keep = 0, n_old = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < kChunkTrips; ++j) {
+            const uint32_t q = first + j * 64u + lane;
+            bool live = false, old = false;
+            if (q < slots) {
+                const Slot v = t[q];
+                live = v.id != kEmpty && v.id != kGone;
+                old = live && (a.now - v.stamp > a.timeout); // unsigned: wraps like the tick counter
+            }
+            keep[j] = __ballot(live && !old);
+            n_keep += (uint32_t)__popcll(keep[j]);
+            n_old += (uint32_t)__popcll(__ballot(old));
+        }
+        uint32_t base = 0;
+        if (lane == 0) {
+            if (n_keep) base = atomicAdd(&a.counters[side], n_keep);
+            if (n_old && a.stats) atomicAdd(&a.stats[kExpired], n_old);
+        }
+        base = (uint32_t)__shfl((int)base, 0, 64);
+        // pass 2: move the survivors, clear every used slot
+#pragma unroll
+        for (uint32_t j = 0; j < kChunkTrips; ++j) {
+            const uint32_t q = first + j * 64u + lane;
+            if (q < slots) {
+                const Slot v = t[q];
+                if (v.id != kEmpty) {
+                    if ((keep[j] >> lane) & 1ull)
+                        a.list[(size_t)side * slots + base + (uint32_t)__popcll(keep[j] & ((1ull << lane) - 1ull))] = v;
+                    t[q].id = kEmpty;
                 }
             }
-            s->id = kEmpty;
+            base += (uint32_t)__popcll(keep[j]);
         }
     }
 }
@@ -121,22 +176,26 @@ __global__ __launch_bounds__(256) void join_reinsert(JoinArgs a)
     }
 }
 
-// arrivals of one side: SIDE 0 = queue 3 (own table 0, partner table 1), SIDE 1 = queue 2
+// arrivals of one side: SIDE 0 = queue 3 (own table 0, partner table 1), SIDE 1 = queue 2.
+// what: 0 stored to wait, 1 matched, 2 no room (or a reserved ID), 3 already waiting on this side, 4 no record
 template <int SIDE>
-__global__ __launch_bounds__(256) void join_arrive(JoinArgs a, const unsigned long long* __restrict__ ids,
-                                                   const uint32_t* __restrict__ vals, uint32_t n)
+__device__ __forceinline__ void arrive_one(const JoinArgs& a, const unsigned long long* __restrict__ ids,
+                                           const uint32_t* __restrict__ vals, uint32_t n, uint32_t g)
 {
     Slot* own = a.table[SIDE];
     Slot* other = a.table[1 - SIDE];
-    for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < n; g += gridDim.x * blockDim.x) {
-        const unsigned long long id = ids[g];
-        const uint32_t val = vals[g];
-        if (id == kEmpty || id == kGone) { // reserved values cannot be stored
-            if (a.stats) atomicAdd(&a.stats[kDropped], 1u);
-            continue;
-        }
+    int what = 4;
+    uint32_t val = 0, pair_val = 0;
+    unsigned long long id = kEmpty;
+    if (g < n) {
+        id = ids[g];
+        val = vals[g];
+        what = 2; // stays so for the two reserved IDs, which cannot be stored
+    }
+    if (id != kEmpty && id != kGone) {
         // partner waiting on the other side?
         bool matched = false;
+        uint32_t pv = 0;
         uint32_t p = slot_of(id, a.mask);
         for (uint32_t tries = 0; tries <= a.mask; ++tries, p = (p + 1u) & a.mask) {
             const unsigned long long seen = other[p].id;
@@ -144,27 +203,39 @@ __global__ __launch_bounds__(256) void join_arrive(JoinArgs a, const unsigned lo
             if (seen == id) {
                 // take it out; only one arrival can win the slot
                 if (atomicCAS(&other[p].id, id, kGone) == id) {
-                    const uint32_t pv = other[p].val;
-                    const uint32_t at = atomicAdd(a.n_pairs, 1u);
-                    if (at < a.pair_cap) {
-                        a.pair_q3[at] = SIDE == 0 ? val : pv;
-                        a.pair_q2[at] = SIDE == 0 ? pv : val;
-                    } else if (a.stats) {
-                        atomicAdd(&a.stats[kPairOverflow], 1u);
-                    }
+                    pv = other[p].val;
                     matched = true;
                 }
                 break;
             }
         }
-        if (matched) continue;
-        bool dup = false;
-        if (!insert_slot(own, a.mask, id, val, a.now, &dup)) {
-            if (a.stats) atomicAdd(&a.stats[kDropped], 1u);
-        } else if (dup && a.stats) {
-            atomicAdd(&a.stats[kDuplicate], 1u);
+        bool dup = false, stored = true;
+        if (!matched) stored = insert_slot(own, a.mask, id, val, a.now, &dup);
+        what = matched ? 1 : (!stored ? 2 : (dup ? 3 : 0));
+        pair_val = pv;
+    }
+    // the wave's pairs take consecutive positions with one atomic
+    const uint32_t at = wave_claim(a.n_pairs, what == 1);
+    if (what == 1) {
+        if (at < a.pair_cap) {
+            a.pair_q3[at] = SIDE == 0 ? val : pair_val;
+            a.pair_q2[at] = SIDE == 0 ? pair_val : val;
         }
     }
+    if (a.stats) {
+        wave_count(&a.stats[kPairOverflow], what == 1 && at >= a.pair_cap);
+        wave_count(&a.stats[kDropped], what == 2);
+        wave_count(&a.stats[kDuplicate], what == 3);
+    }
+}
+
+template <int SIDE>
+__global__ __launch_bounds__(256) void join_arrive(JoinArgs a, const unsigned long long* __restrict__ ids,
+                                                   const uint32_t* __restrict__ vals, uint32_t n)
+{
+    const uint32_t rounded = (n + 63u) & ~63u; // whole waves stay in the loop together
+    for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < rounded; g += gridDim.x * blockDim.x)
+        arrive_one<SIDE>(a, ids, vals, n, g);
 }
 
 // live records of one side -> arrays, in no particular order
@@ -258,7 +329,7 @@ extern "C" int sf_join_step(sf_ctx* ctx, const sf_join_table* table, uint32_t no
     a.stats = stats;
     join_zero<<<1, 64, 0, ctx->stream>>>(counters, n_pairs, stats);
     SF_LAUNCH_CHECK(ctx, "join_zero");
-    join_collect<<<grid_for(2ull * slots), 256, 0, ctx->stream>>>(a);
+    join_collect<<<grid_for(2ull * slots / kChunkTrips), 256, 0, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "join_collect");
     join_reinsert<<<grid_for(slots), 256, 0, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "join_reinsert");
