@@ -163,18 +163,20 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     const uint32_t leaf_base = recs_upto(full_pairs); // record index of position 0 on tree level 2*full_pairs
     const uint32_t n_leaf = 1u << depth;
 
-    // two visits from one record; o is the byte offset of the record inside its tree
+    // two visits from one record; o is the byte offset of the record inside its tree.  The child's
+    // feature is fetched after the parent's test (two shared-memory reads per record, the second
+    // dependent on the first) rather than both children's up front (three independent reads): the
+    // shared-memory pipe is the scarcer resource here, and the trees in flight cover the latency.
 #define SF_PAIR_STEP(REC, O)                                                                              \
     do {                                                                                                  \
         const uint32_t fw = (REC).w;                                                                      \
         const float x0 = *reinterpret_cast<const float*>(xlane + ((fw & 0xFFu) << kColShift));            \
-        const float x1 = *reinterpret_cast<const float*>(xlane + (((fw >> 8) & 0xFFu) << kColShift));     \
-        const float x2 = *reinterpret_cast<const float*>(xlane + ((fw >> 16) << kColShift));              \
         const bool r0 = !(x0 <= __uint_as_float((REC).x));                                                \
-        const bool r1 = !(x1 <= __uint_as_float((REC).y));                                                \
-        const bool r2 = !(x2 <= __uint_as_float((REC).z));                                                \
-        const uint32_t inc_l = r1 ? 32u : 16u, inc_r = r2 ? 64u : 48u;                                    \
-        (O) = 4u * (O) + (r0 ? inc_r : inc_l);                                                            \
+        const uint32_t fc = r0 ? (fw >> 16) : ((fw >> 8) & 0xFFu);                                        \
+        const float tc = __uint_as_float(r0 ? (REC).z : (REC).y);                                         \
+        const float xc = *reinterpret_cast<const float*>(xlane + (fc << kColShift));                      \
+        const bool rc = !(xc <= tc);                                                                      \
+        (O) = 4u * (O) + (r0 ? 48u : 16u) + (rc ? 16u : 0u);                                              \
     } while (0)
 
     // lane group g walks trees g, g+S, ...; every group runs the same number of rounds so that
