@@ -27,10 +27,10 @@ F32_VECTOR_PEAK_TFLOPS = 157.3
 # WRITE_SIZE scaled by a 256 MiB reference copy (profiles/cfg2_1m_hbm_traffic.txt).  Each entry is tied to
 # the kernel source it was measured on: once that file changes, the figure is reported as null again.
 MEASURED_TRAFFIC = {
-    "sf_featurize": ("featurize.hip", "f0e5fb7c57c0930d", 392450020),
-    "sf_fast_infer": ("fast_infer.hip", "5d802e2a737a189a", 375158271),
-    "sf_route": ("route.hip", "4e2a63cd8c41434f", 5062754),
-    "sf_slow_infer": ("slow_fused.hip", "e97733a8f590acea", 54114572),
+    "sf_featurize": ("featurize.hip", "f0e5fb7c57c0930d", 392449651),
+    "sf_fast_infer": ("fast_infer.hip", "f8f62591269af98f", 375174499),
+    "sf_route": ("route.hip", "f58da4221819e5b2", 5108805),
+    "sf_slow_infer": ("slow_fused.hip", "080ae2c67eb6d8aa", 54118458),
 }
 
 

@@ -163,20 +163,31 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     const uint32_t leaf_base = recs_upto(full_pairs); // record index of position 0 on tree level 2*full_pairs
     const uint32_t n_leaf = 1u << depth;
 
-    // two visits from one record; o is the byte offset of the record inside its tree.  The child's
-    // feature is fetched after the parent's test (two shared-memory reads per record, the second
-    // dependent on the first) rather than both children's up front (three independent reads): the
-    // shared-memory pipe is the scarcer resource here, and the trees in flight cover the latency.
+    // two visits from one record; o is the byte offset of the record inside its tree.
+    // One lane per flow (S = 1, eight or more waves per compute unit): the child's feature is fetched
+    // after the parent's test (two shared-memory reads per record, the second dependent on the first):
+    // the shared-memory pipe is the scarcer resource there and the resident waves cover the latency.
+    // Lanes sharing a flow (S = 2: forests whose shared-memory needs leave few waves resident): all
+    // three features up front (three independent reads), which is faster when latency binds.
 #define SF_PAIR_STEP(REC, O)                                                                              \
     do {                                                                                                  \
         const uint32_t fw = (REC).w;                                                                      \
         const float x0 = *reinterpret_cast<const float*>(xlane + ((fw & 0xFFu) << kColShift));            \
         const bool r0 = !(x0 <= __uint_as_float((REC).x));                                                \
-        const uint32_t fc = r0 ? (fw >> 16) : ((fw >> 8) & 0xFFu);                                        \
-        const float tc = __uint_as_float(r0 ? (REC).z : (REC).y);                                         \
-        const float xc = *reinterpret_cast<const float*>(xlane + (fc << kColShift));                      \
-        const bool rc = !(xc <= tc);                                                                      \
-        (O) = 4u * (O) + (r0 ? 48u : 16u) + (rc ? 16u : 0u);                                              \
+        if (S == 1) {                                                                                     \
+            const uint32_t fc = r0 ? (fw >> 16) : ((fw >> 8) & 0xFFu);                                    \
+            const float tc = __uint_as_float(r0 ? (REC).z : (REC).y);                                     \
+            const float xc = *reinterpret_cast<const float*>(xlane + (fc << kColShift));                  \
+            const bool rc = !(xc <= tc);                                                                  \
+            (O) = 4u * (O) + (r0 ? 48u : 16u) + (rc ? 16u : 0u);                                          \
+        } else {                                                                                          \
+            const float x1 = *reinterpret_cast<const float*>(xlane + (((fw >> 8) & 0xFFu) << kColShift)); \
+            const float x2 = *reinterpret_cast<const float*>(xlane + ((fw >> 16) << kColShift));          \
+            const bool r1 = !(x1 <= __uint_as_float((REC).y));                                            \
+            const bool r2 = !(x2 <= __uint_as_float((REC).z));                                            \
+            const uint32_t inc_l = r1 ? 32u : 16u, inc_r = r2 ? 64u : 48u;                                \
+            (O) = 4u * (O) + (r0 ? inc_r : inc_l);                                                        \
+        }                                                                                                 \
     } while (0)
 
     // lane group g walks trees g, g+S, ...; every group runs the same number of rounds so that
