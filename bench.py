@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 F32_VECTOR_PEAK_TFLOPS = 157.3
+# What bounds the tree walk is gather throughput, not HBM: a node visit needs one 4-byte feature gather from
+# shared memory (5 cycles per 64 lanes, measured with a micro-benchmark on this chip) and half a 16-byte record
+# gather (9.5 cycles when it comes from shared memory, more from the caches).  If every record came from shared
+# memory a compute unit could retire 64 / (5 + 9.5 / 2) lane-visits per clock; 256 units at 2.4 GHz:
+GATHER_BOUND_VISITS_PER_S = 64.0 / (5.0 + 9.5 / 2.0) * 256 * 2.4e9
 
 # HBM bytes per launch on the headline workload (config 2 at its full size), from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE scaled by a 256 MiB reference copy (profiles/cfg2_1m_hbm_traffic.txt).  Each entry is tied to
@@ -413,7 +418,8 @@ def main():
     kernels = {
         "sf_featurize": dict(hbm("sf_featurize", k1b, avg[0]), ms=float(avg[0]), bytes=k1b),
         "sf_fast_infer": dict(hbm("sf_fast_infer", k2b, avg[1]), ms=float(avg[1]), bytes=k2b, node_visits=visits,
-                              visits_per_s=visits / (avg[1] * 1e-3)),
+                              visits_per_s=visits / (avg[1] * 1e-3), gather_bound_visits_per_s=GATHER_BOUND_VISITS_PER_S,
+                              gather_frac=visits / (avg[1] * 1e-3) / GATHER_BOUND_VISITS_PER_S),
         "sf_route": dict(hbm("sf_route", k3b, avg[2]), ms=float(avg[2]), bytes=k3b),
     }
     tf = flops / (avg[3] * 1e-3) / 1e12
