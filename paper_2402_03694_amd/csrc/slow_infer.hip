@@ -223,26 +223,67 @@ __global__ __launch_bounds__(256) void f32_input(F32Args a, float* __restrict__ 
     }
 }
 
-// out[r][o] = act(sum_k in[r][k] * w[o][k] + b[o]); 64 rows x 4 outputs per block pass
+// out[r][o] = act(sum_k in[r][k] * w[o][k] + b[o]) in binary32, the sum taken in order of k (one multiply
+// and one add per term, each rounded).  A block computes a 64 x 64 tile of outputs from K-slabs of 16 staged
+// in shared memory; a thread owns a 4 x 4 patch (rows ty + 16 i, columns tx + 16 j).
+constexpr int kF32Tile = 64, kF32Slab = 16;
+
 __global__ __launch_bounds__(256) void f32_layer(const uint32_t* esc_count, uint32_t esc_cap, uint32_t row_begin,
                                                  uint32_t rows_cap, const float* __restrict__ in, uint32_t K,
                                                  const float* __restrict__ w, const float* __restrict__ bias,
                                                  uint32_t N, float* __restrict__ out, int relu)
 {
+    __shared__ float As[kF32Slab][kF32Tile + 1]; // [k][row]
+    __shared__ float Ws[kF32Slab][kF32Tile + 1]; // [k][column]
     uint32_t total = *esc_count;
     total = total < esc_cap ? total : esc_cap;
     if (row_begin >= total) return;
     uint32_t rows = total - row_begin;
     rows = rows < rows_cap ? rows : rows_cap;
-    const uint64_t n = (uint64_t)rows * N;
-    for (uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n; g += (uint64_t)gridDim.x * blockDim.x) {
-        const uint32_t r = (uint32_t)(g / N), o = (uint32_t)(g % N);
-        const float* x = in + (size_t)r * K;
-        const float* wr = w + (size_t)o * K;
-        float acc = 0.f;
-        for (uint32_t k = 0; k < K; ++k) acc += x[k] * wr[k];
-        acc += bias[o];
-        out[g] = (relu && acc < 0.f) ? 0.f : acc;
+    const uint32_t r0 = blockIdx.x * kF32Tile, c0 = blockIdx.y * kF32Tile;
+    if (r0 >= rows) return;
+    const uint32_t tid = threadIdx.x, tx = tid & 15u, ty = tid >> 4;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (uint32_t k0 = 0; k0 < K; k0 += kF32Slab) {
+        // 64 x 16 values of each operand, four per thread: element e -> (row e / 16, k e % 16)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t e = tid + 256u * q, rr = e >> 4, kk = e & 15u;
+            const bool kin = k0 + kk < K;
+            As[kk][rr] = (kin && r0 + rr < rows) ? in[(size_t)(r0 + rr) * K + k0 + kk] : 0.f;
+            Ws[kk][rr] = (kin && c0 + rr < N) ? w[(size_t)(c0 + rr) * K + k0 + kk] : 0.f;
+        }
+        __syncthreads();
+        const uint32_t kn = K - k0 < (uint32_t)kF32Slab ? K - k0 : (uint32_t)kF32Slab;
+        for (uint32_t kk = 0; kk < kn; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty + 16 * i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Ws[kk][tx + 16 * j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t r = r0 + ty + 16 * i;
+        if (r >= rows) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t o = c0 + tx + 16 * j;
+            if (o < N) {
+                const float y = acc[i][j] + bias[o];
+                out[(size_t)r * N + o] = (relu && y < 0.f) ? 0.f : y;
+            }
+        }
     }
 }
 
@@ -461,13 +502,14 @@ int run_slow(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows, 
         auto blocks = [&](uint64_t n) { uint64_t b = (n + 255) / 256; return (uint32_t)(b > 16384 ? 16384 : (b ? b : 1)); };
         f32_input<<<blocks((uint64_t)R * mlp->n_in), 256, 0, ctx->stream>>>(f, z);
         SF_LAUNCH_CHECK(ctx, "f32_input");
-        f32_layer<<<blocks((uint64_t)R * mlp->n_h1), 256, 0, ctx->stream>>>(esc_count, esc_cap, begin, R, z, mlp->n_in,
+        auto tiles = [&](uint32_t n_out) { return dim3((R + kF32Tile - 1) / kF32Tile, (n_out + kF32Tile - 1) / kF32Tile); };
+        f32_layer<<<tiles(mlp->n_h1), 256, 0, ctx->stream>>>(esc_count, esc_cap, begin, R, z, mlp->n_in,
                                                                             (const float*)mlp->w1, mlp->b1, mlp->n_h1, h1, 1);
         SF_LAUNCH_CHECK(ctx, "f32_layer 1");
-        f32_layer<<<blocks((uint64_t)R * mlp->n_h2), 256, 0, ctx->stream>>>(esc_count, esc_cap, begin, R, h1, mlp->n_h1,
+        f32_layer<<<tiles(mlp->n_h2), 256, 0, ctx->stream>>>(esc_count, esc_cap, begin, R, h1, mlp->n_h1,
                                                                             (const float*)mlp->w2, mlp->b2, mlp->n_h2, h2, 1);
         SF_LAUNCH_CHECK(ctx, "f32_layer 2");
-        f32_layer<<<blocks((uint64_t)R * mlp->n_classes), 256, 0, ctx->stream>>>(
+        f32_layer<<<tiles(mlp->n_classes), 256, 0, ctx->stream>>>(
             esc_count, esc_cap, begin, R, h2, mlp->n_h2, (const float*)mlp->w3, mlp->b3, mlp->n_classes, lg, 0);
         SF_LAUNCH_CHECK(ctx, "f32_layer 3");
         f32_argmax<<<blocks(R), 256, 0, ctx->stream>>>(scatter ? scatter : esc_idx, esc_count, esc_cap, begin, R, lg,
