@@ -282,8 +282,8 @@ def main():
                     help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus %d is not supported (flows would be sharded "
-              "across devices with the models replicated, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus %d is not supported (across devices the flows would be "
+              "sharded and the models replicated, with no exchange on the hot path)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
