@@ -103,11 +103,12 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     const uint32_t F = a.n_features, C = a.n_classes, T = a.n_trees;
     const uint32_t top_recs = recs_upto(a.top_pairs);      // records per tree held in shared memory
     float* xT = reinterpret_cast<float*>(smem_raw);                          // [F][FPB]
-    // vote counters, 32 / vote_bits classes per word, one column per LANE: [vote_words][BS]
+    // vote counters, 32 / vote_bits classes per word, one column per FLOW: [vote_words][FPB]; the S lanes of
+    // a flow add to it with shared-memory atomics (fields cannot carry into each other: a count is at most n_trees)
     const uint32_t per_shift = a.vote_bits == 8 ? 2u : 1u; // log2(counters per word)
     const uint32_t vote_words = GBDT ? C : (C + (1u << per_shift) - 1u) >> per_shift; // boosted: one float per class
     uint32_t* vT = reinterpret_cast<uint32_t*>(xT + (size_t)F * FPB);
-    uint4* topT = reinterpret_cast<uint4*>(vT + (size_t)vote_words * BS);    // [T][top_recs]
+    uint4* topT = reinterpret_cast<uint4*>(vT + (size_t)vote_words * FPB);   // [T][top_recs]
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t grp = lane / FPW;                       // which share of the trees this lane walks
     const uint32_t slot = wave * FPW + (lane % FPW);       // flow slot in the block's tile
@@ -141,9 +142,9 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
         }
     }
     if (GBDT) {
-        for (uint32_t c = 0; c < C; ++c) vT[c * BS + tid] = __float_as_uint(a.base ? a.base[c] : 0.f);
+        for (uint32_t c = 0; c < C; ++c) vT[c * FPB + slot] = __float_as_uint(a.base ? a.base[c] : 0.f);
     } else {
-        for (uint32_t c = 0; c < vote_words; ++c) vT[c * BS + tid] = 0;
+        for (uint32_t c = grp; c < vote_words; c += S) vT[c * FPB + slot] = 0;
     }
     const uint32_t n_rec = recs_upto(pair_levels(a.depth));
     const uint4* recs = reinterpret_cast<const uint4*>(a.recs);
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     const uint32_t lds_pairs = a.top_pairs < full_pairs ? a.top_pairs : full_pairs;
     const bool odd = depth & 1u;
     const char* xlane = reinterpret_cast<const char*>(xT) + slot * 4u; // the flow's column
-    uint32_t* vcol = vT + tid;
+    uint32_t* vcol = vT + slot;
     const uint32_t rec_bytes = n_rec * 16u, top_bytes = top_recs * 16u;
     const uint32_t leaf_base = recs_upto(full_pairs); // record index of position 0 on tree level 2*full_pairs
     const uint32_t n_leaf = 1u << depth;
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
 #pragma unroll
             for (int u = 0; u < kIlp; ++u) { // ascending u = ascending tree: the order of the sum
                 if (tv[u]) {
-                    float* m = reinterpret_cast<float*>(&vcol[(tt[u] % C) * BS]);
+                    float* m = reinterpret_cast<float*>(&vcol[(tt[u] % C) * FPB]);
                     *m = *m + val[u];
                     if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + tt[u]] = (uint16_t)leaf[u];
                 }
@@ -260,32 +261,32 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
             if (tv[u]) {
                 const uint32_t l = lab[u] < C ? lab[u] : C - 1u; // clamp: a bad label must not leave the tile
                 // only this lane touches its column; the add is one shared-memory instruction
-                atomicAdd(&vcol[(l >> per_shift) * BS], 1u << ((l & ((1u << per_shift) - 1u)) * a.vote_bits));
+                atomicAdd(&vcol[(l >> per_shift) * FPB], 1u << ((l & ((1u << per_shift) - 1u)) * a.vote_bits));
                 if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + tt[u]] = (uint16_t)leaf[u];
             }
         }
     }
 #undef SF_PAIR_STEP
-    if (S > 1) __syncthreads(); // the S partial vote columns of a flow are summed by its first lane
+    if (S > 1) __syncthreads(); // all lanes of a flow have added their votes before its first lane reads them
     if (!live || grp != 0) return;
     if (GBDT) {
         const float* mcol = reinterpret_cast<const float*>(vcol);
         uint32_t bc = 0;
         float bm = mcol[0];
         for (uint32_t c = 1; c < C; ++c) {
-            const float m = mcol[c * BS];
+            const float m = mcol[c * FPB];
             if (m > bm) { // strict: the lowest class wins a tie
                 bm = m;
                 bc = c;
             }
         }
         double z = 0.0;
-        for (uint32_t c = 0; c < C; ++c) z += exp((double)mcol[c * BS] - (double)bm);
+        for (uint32_t c = 0; c < C; ++c) z += exp((double)mcol[c * FPB] - (double)bm);
         double sc;
         if (a.score_kind == SF_SCORE_ENTROPY) {
             double h = 0.0;
             for (uint32_t c = 0; c < C; ++c) {
-                const double p = exp((double)mcol[c * BS] - (double)bm) / z;
+                const double p = exp((double)mcol[c * FPB] - (double)bm) / z;
                 if (p > 0.0) h -= p * log(p);
             }
             sc = h;
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
             sc = 1.0 - 1.0 / z; // the largest probability is exp(0) / z
         }
         if (a.margins)
-            for (uint32_t c = 0; c < C; ++c) a.margins[(size_t)i * C + c] = mcol[c * BS];
+            for (uint32_t c = 0; c < C; ++c) a.margins[(size_t)i * C + c] = mcol[c * FPB];
         a.pred[i] = (uint16_t)bc;
         a.score[i] = (float)sc;
         if (a.labels) a.labels[row] = (uint16_t)bc;
@@ -302,9 +303,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
     uint32_t best = 0, bestv = 0;
     const uint32_t vmask = (1u << a.vote_bits) - 1u;
     for (uint32_t w = 0; w < vote_words; ++w) {
-        uint32_t word = 0; // packed fields cannot overflow: the sum over groups is at most n_trees
-#pragma unroll
-        for (int g = 0; g < S; ++g) word += vT[w * BS + tid + g * FPW];
+        const uint32_t word = vT[w * FPB + slot];
         for (uint32_t k = 0; k < (1u << per_shift); ++k) {
             const uint32_t c = (w << per_shift) + k;
             if (c < C) {
@@ -444,7 +443,7 @@ int run_trees(sf_ctx* ctx, const char* who, const float* feat, uint32_t feat_ld,
     // for `split` lanes per flow: how many pair-levels of records fit, and the block's shared memory.
     // The top records may use what is left of a third, else of a half, else of the whole shared memory.
     auto plan = [&](uint32_t split) {
-        const size_t fixed = (size_t)a.n_features * 4 * (256 / split) + (size_t)result_words * 4 * 256;
+        const size_t fixed = ((size_t)a.n_features + result_words) * 4 * (256 / split);
         size_t budget = 160 * 1024 / 3 - 256;
         if (fixed + (size_t)a.n_trees * 16 > budget) budget = 80 * 1024 - 512;
         if (fixed + (size_t)a.n_trees * 16 > budget) budget = 160 * 1024 - 1024;
