@@ -2,16 +2,21 @@
 // (Section 3.1 of the paper) and the integer form of the least-confidence score of
 // Section 3.2 (top_votes = max_y votes[y]; LC = 1 - top_votes / n_trees).
 //
-// Work split: one lane owns one flow.  Its feature row sits in shared memory as a column,
-// [feature][lane], so the data-dependent fetch x[feat] of every lane of a wave lands in its own
-// bank.  What bounds the walk is the number of vector-memory instructions (a compute unit
-// retires a 64-lane gather roughly every 16 cycles whatever it hits), so the forest is re-packed
-// once per call into 16-byte records that hold TWO levels: a node and both its children (three
-// thresholds, three feature indices).  One 16-byte load then serves two visits.  Records form a
-// quaternary heap per tree (record r has children 4r+1..4r+4); the records of the top levels of
-// every tree are staged in shared memory, the deeper ones come through the cache; the leaf
-// label is one byte load at the end.  Several trees are walked at once per lane to keep
-// independent loads in flight.  Votes are integers in shared memory; nothing here rounds.
+// Also here: the same walk over the flows of a list (the middle tier of a three-tier cascade)
+// and the boosted-tree form of the fast model (Section 4.1), whose leaves hold margins.
+//
+// Work split: one lane owns one flow (or 2 or 4 lanes share one and split the trees, where
+// shared memory would otherwise leave too few waves resident).  The flow's feature row sits in
+// shared memory as a column, [feature][flow], so the data-dependent fetch x[feat] of every lane
+// of a wave lands in its own bank.  What bounds the walk is gather throughput, of the caches'
+// address path (a compute unit retires a 64-lane gather every 16 to 57 cycles, by how many
+// cache lines it touches) and of shared memory alike, so the forest is re-packed once per call
+// into 16-byte records that hold TWO levels: a node and both its children (three thresholds,
+// three feature indices).  One 16-byte load then serves two visits.  Records form a quaternary
+// heap per tree (record r has children 4r+1..4r+4); the records of the top levels of every tree
+// are staged in shared memory, the deeper ones come through the cache; the leaf label is one
+// byte load at the end.  Eight trees are walked at once per lane to keep independent loads in
+// flight.  Votes are integers in shared memory; nothing in the voting form rounds.
 #include "common.h"
 
 namespace {
