@@ -122,6 +122,8 @@ def three_tier(args, cfg):
     d_tree, d_forest, d_mlp = sf.tree_to_device(tree, dev), sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
     ctx.sf_validate_tree(d_tree)
     ctx.sf_validate_forest(d_forest)
+    ctx.sf_forest_pack(d_forest)       # the models are laid out for the kernels once, not per batch
+    ctx.sf_mlp_order(d_mlp)
     names = ["sf_featurize", "sf_fastest_infer", "sf_route_ratio", "sf_fast_infer_subset", "sf_route_subset",
              "sf_slow_infer"]
 
@@ -321,15 +323,18 @@ def main():
     gbdt = cfg.fast_kind == "gbdt"
     mlp = synth.make_mlp(cfg, None if cfg.raw_pkts else calib)
     d_mlp = sf.mlp_to_device(mlp, dev)
+    ctx.sf_mlp_order(d_mlp)            # the models are laid out for the kernels once, not per batch
     ctx.sf_validate_packets(d_pk)
     if gbdt:
         d_model = sf.gbdt_to_device(synth.make_gbdt(cfg, calib), dev)
+        ctx.sf_gbdt_pack(d_model)
         kind = sf.SF_SCORE_ENTROPY if cfg.score == "entropy" else sf.SF_SCORE_LC
         score = torch.empty(n, dtype=torch.float32, device=dev)
     else:
         forest = synth.make_forest(cfg, calib)
         d_forest = sf.forest_to_device(forest, dev)
         ctx.sf_validate_forest(d_forest)
+        ctx.sf_forest_pack(d_forest)
 
     # gate threshold: explicit, from theta, or the target-portion rule on this run's own scores
     # (target-portion rule of Section 3.2: the library histograms the integer score on the device and

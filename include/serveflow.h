@@ -128,7 +128,16 @@ typedef struct {
     const uint16_t* node_feat; /* [n_trees][2^depth - 1], values < n_features               */
     const float* node_thr;     /* [n_trees][2^depth - 1]                                    */
     const uint8_t* leaf_label; /* [n_trees][2^depth], values < n_classes                    */
+    const void* packed;        /* optional: what sf_forest_pack wrote for these node arrays;
+                                  NULL = the nodes are re-packed into the workspace per call */
 } sf_forest;
+
+/* The kernels walk a packed copy of node_feat / node_thr.  A caller that keeps a model across
+ * calls can have it made once: sf_forest_pack writes sf_forest_packed_bytes(n_trees, depth)
+ * bytes to packed (device, 256-byte aligned, caller-owned) on the context's stream; set
+ * forest->packed to it afterwards (and leave the node arrays unchanged while it is in use). */
+size_t sf_forest_packed_bytes(uint32_t n_trees, uint32_t depth);
+int sf_forest_pack(sf_ctx* ctx, const sf_forest* forest, void* packed);
 
 /* feat: [n_flows][feat_ld], n_features <= feat_ld.  pred, top_votes: [n_flows].
  * votes: optional [n_flows][n_classes]; leaf_idx: optional [n_flows][n_trees] (for parity
@@ -261,7 +270,10 @@ typedef struct {
     const float* node_thr;     /* [n_trees][2^depth - 1]                                       */
     const float* leaf_value;   /* [n_trees][2^depth]                                           */
     const float* base;         /* [n_classes] initial margins, or NULL for zeros               */
+    const void* packed;        /* optional, as in sf_forest (sf_gbdt_pack, same size formula)  */
 } sf_gbdt;
+
+int sf_gbdt_pack(sf_ctx* ctx, const sf_gbdt* model, void* packed);
 
 enum { SF_SCORE_LC = 0, SF_SCORE_ENTROPY = 1 };
 
@@ -343,7 +355,15 @@ typedef struct {
     const void *w1, *w2, *w3;         /* row-major [out][in]; float or bfloat16 (uint16 bit
                                          patterns) according to dtype                        */
     const float *b1, *b2, *b3;        /* [out]                                               */
+    const void* ordered;              /* optional (SF_BF16 only): what sf_mlp_order wrote for these
+                                         weights; NULL = re-ordered into the workspace per call */
 } sf_mlp;
+
+/* The bfloat16 kernels read the weights in MFMA operand order.  sf_mlp_order writes that copy
+ * of w1, w2, w3 (sf_mlp_ordered_bytes(mlp) bytes; 0 for SF_F32) to ordered (device, 256-byte
+ * aligned, caller-owned) on the context's stream; set mlp->ordered to it afterwards. */
+size_t sf_mlp_ordered_bytes(const sf_mlp* mlp);
+int sf_mlp_order(sf_ctx* ctx, const sf_mlp* mlp, void* ordered);
 
 /* esc_idx / esc_count: as written by sf_route (device).  At most esc_cap flows are
  * processed (the capacity of logits; pass n_flows to process all); flows beyond it keep the

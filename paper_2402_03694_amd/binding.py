@@ -24,7 +24,8 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_vmin_for_target", "sf_fastest_infer", "sf_validate_tree", "sf_route_ratio",
            "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
            "sf_class_score_histogram", "sf_per_class_thresholds", "sf_join_table_bytes", "sf_join_workspace_bytes",
-           "sf_join_step", "sf_join_pending", "sf_slow_infer_pairs")
+           "sf_join_step", "sf_join_pending", "sf_slow_infer_pairs", "sf_forest_packed_bytes", "sf_forest_pack",
+           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order")
 
 
 class SfPackets(ctypes.Structure):
@@ -43,7 +44,7 @@ class SfForest(ctypes.Structure):
     _fields_ = [("n_trees", ctypes.c_uint32), ("depth", ctypes.c_uint32),
                 ("n_classes", ctypes.c_uint32), ("n_features", ctypes.c_uint32),
                 ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p),
-                ("leaf_label", ctypes.c_void_p)]
+                ("leaf_label", ctypes.c_void_p), ("packed", ctypes.c_void_p)]
 
 
 class SfTree(ctypes.Structure):
@@ -54,7 +55,7 @@ class SfTree(ctypes.Structure):
 class SfGbdt(ctypes.Structure):
     _fields_ = [("n_trees", ctypes.c_uint32), ("depth", ctypes.c_uint32), ("n_classes", ctypes.c_uint32),
                 ("n_features", ctypes.c_uint32), ("node_feat", ctypes.c_void_p), ("node_thr", ctypes.c_void_p),
-                ("leaf_value", ctypes.c_void_p), ("base", ctypes.c_void_p)]
+                ("leaf_value", ctypes.c_void_p), ("base", ctypes.c_void_p), ("packed", ctypes.c_void_p)]
 
 
 class SfJoinTable(ctypes.Structure):
@@ -69,7 +70,8 @@ class SfMlp(ctypes.Structure):
                 ("n_classes", ctypes.c_uint32), ("dtype", ctypes.c_int),
                 ("mu", ctypes.c_void_p), ("inv_sigma", ctypes.c_void_p), ("clamp", ctypes.c_float),
                 ("w1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("w3", ctypes.c_void_p),
-                ("b1", ctypes.c_void_p), ("b2", ctypes.c_void_p), ("b3", ctypes.c_void_p)]
+                ("b1", ctypes.c_void_p), ("b2", ctypes.c_void_p), ("b3", ctypes.c_void_p),
+                ("ordered", ctypes.c_void_p)]
 
 
 class ServeFlowError(RuntimeError):
@@ -122,6 +124,16 @@ def load_library() -> ctypes.CDLL:
     lib.sf_per_class_thresholds.restype = ctypes.c_int
     lib.sf_per_class_thresholds.argtypes = [ctypes.POINTER(ctypes.c_uint32), u32, u32, ctypes.c_double,
                                             ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_double)]
+    lib.sf_forest_packed_bytes.restype = sz
+    lib.sf_forest_packed_bytes.argtypes = [u32, u32]
+    lib.sf_forest_pack.restype = ctypes.c_int
+    lib.sf_forest_pack.argtypes = [vp, ctypes.POINTER(SfForest), vp]
+    lib.sf_gbdt_pack.restype = ctypes.c_int
+    lib.sf_gbdt_pack.argtypes = [vp, ctypes.POINTER(SfGbdt), vp]
+    lib.sf_mlp_ordered_bytes.restype = sz
+    lib.sf_mlp_ordered_bytes.argtypes = [ctypes.POINTER(SfMlp)]
+    lib.sf_mlp_order.restype = ctypes.c_int
+    lib.sf_mlp_order.argtypes = [vp, ctypes.POINTER(SfMlp), vp]
     lib.sf_slow_infer_pairs.restype = ctypes.c_int
     lib.sf_slow_infer_pairs.argtypes = [vp, vp, u32, u32, vp, vp, vp, u32, u32, ctypes.POINTER(SfMlp), vp, vp]
     lib.sf_join_table_bytes.restype = sz
@@ -258,6 +270,7 @@ class DeviceForest:
     def __init__(self, n_trees, depth, n_classes, n_features, node_feat, node_thr, leaf_label):
         self.n_trees, self.depth, self.n_classes, self.n_features = n_trees, depth, n_classes, n_features
         self.node_feat, self.node_thr, self.leaf_label = node_feat, node_thr, leaf_label
+        self.packed = None   # set by ServeFlow.sf_forest_pack
 
     def c_struct(self) -> SfForest:
         s = SfForest()
@@ -265,6 +278,7 @@ class DeviceForest:
         s.node_feat = _ptr(self.node_feat, torch.int16).value
         s.node_thr = _ptr(self.node_thr, torch.float32).value
         s.leaf_label = _ptr(self.leaf_label, torch.uint8).value
+        s.packed = self.packed.data_ptr() if self.packed is not None else None
         return s
 
 
@@ -286,6 +300,7 @@ class DeviceGbdt:
     def __init__(self, n_trees, depth, n_classes, n_features, node_feat, node_thr, leaf_value, base=None):
         self.n_trees, self.depth, self.n_classes, self.n_features = n_trees, depth, n_classes, n_features
         self.node_feat, self.node_thr, self.leaf_value, self.base = node_feat, node_thr, leaf_value, base
+        self.packed = None   # set by ServeFlow.sf_gbdt_pack
 
     def c_struct(self) -> SfGbdt:
         s = SfGbdt()
@@ -294,6 +309,7 @@ class DeviceGbdt:
         s.node_thr = _ptr(self.node_thr, torch.float32).value
         s.leaf_value = _ptr(self.leaf_value, torch.float32).value
         s.base = _ptr(self.base, torch.float32).value if self.base is not None else None
+        s.packed = self.packed.data_ptr() if self.packed is not None else None
         return s
 
 
@@ -304,6 +320,7 @@ class DeviceMlp:
         self.dims, self.dtype = tuple(dims), dtype
         self.w1, self.b1, self.w2, self.b2, self.w3, self.b3 = w1, b1, w2, b2, w3, b3
         self.mu, self.inv_sigma, self.clamp = mu, inv_sigma, clamp
+        self.ordered = None  # set by ServeFlow.sf_mlp_order
 
     def c_struct(self) -> SfMlp:
         s = SfMlp()
@@ -315,6 +332,7 @@ class DeviceMlp:
         s.clamp = self.clamp
         s.w1, s.w2, s.w3 = (_ptr(w, wd).value for w in (self.w1, self.w2, self.w3))
         s.b1, s.b2, s.b3 = (_ptr(b, torch.float32).value for b in (self.b1, self.b2, self.b3))
+        s.ordered = self.ordered.data_ptr() if self.ordered is not None else None
         return s
 
 
@@ -396,6 +414,36 @@ class ServeFlow:
         n = int(top_votes.shape[0]) if n_flows is None else n_flows
         self._check(self._lib.sf_route(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr, len(vm),
                                        _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    # ---- models prepared once instead of per call ---------------------------------------------
+    def _aligned_bytes(self, n: int) -> torch.Tensor:
+        buf = torch.empty(n + 256, dtype=torch.uint8, device=self.device)
+        off = (-buf.data_ptr()) % 256
+        return buf[off:off + n]
+
+    def sf_forest_pack(self, forest: DeviceForest):
+        forest.packed = None
+        f = forest.c_struct()
+        buf = self._aligned_bytes(int(self._lib.sf_forest_packed_bytes(forest.n_trees, forest.depth)))
+        self._check(self._lib.sf_forest_pack(self._h, ctypes.byref(f), ctypes.c_void_p(buf.data_ptr())))
+        forest.packed = buf
+
+    def sf_gbdt_pack(self, model: "DeviceGbdt"):
+        model.packed = None
+        m = model.c_struct()
+        buf = self._aligned_bytes(int(self._lib.sf_forest_packed_bytes(model.n_trees, model.depth)))
+        self._check(self._lib.sf_gbdt_pack(self._h, ctypes.byref(m), ctypes.c_void_p(buf.data_ptr())))
+        model.packed = buf
+
+    def sf_mlp_order(self, mlp: DeviceMlp):
+        mlp.ordered = None
+        m = mlp.c_struct()
+        n = int(self._lib.sf_mlp_ordered_bytes(ctypes.byref(m)))
+        if n == 0:
+            return                       # nothing to prepare for this model (binary32)
+        buf = self._aligned_bytes(n)
+        self._check(self._lib.sf_mlp_order(self._h, ctypes.byref(m), ctypes.c_void_p(buf.data_ptr())))
+        mlp.ordered = buf
 
     # ---- the tier in front of the fast model and the list forms of steps 2-4 ----------------
     def sf_fastest_infer(self, feat: torch.Tensor, tree: DeviceTree, pred: torch.Tensor, top_count: torch.Tensor,

@@ -364,6 +364,7 @@ struct TreeModel {
     const uint8_t* leaf_label;
     const float* leaf_value;
     const float* base;
+    const void* packed; // records made earlier by sf_forest_pack / sf_gbdt_pack, or NULL
 };
 
 struct Outputs {
@@ -376,6 +377,27 @@ struct Outputs {
     float* score;
     int score_kind;
 };
+
+int pack_into(sf_ctx* ctx, const TreeModel& m, PairRec* out)
+{
+    const uint64_t total = (uint64_t)m.n_trees * recs_upto(pair_levels(m.depth));
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    pack_forest<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(m.n_trees, m.depth, m.n_features, m.node_feat, m.node_thr, out);
+    SF_LAUNCH_CHECK(ctx, "pack_forest");
+    return SF_OK;
+}
+
+int check_model(sf_ctx* ctx, const char* who, const TreeModel& m)
+{
+    if (m.depth < 1 || m.depth > SF_MAX_TREE_DEPTH)
+        return sf::fail(ctx, SF_EINVAL, "%s: depth %u outside 1..%d", who, m.depth, SF_MAX_TREE_DEPTH);
+    if (m.n_trees < 1 || m.n_trees > 65535) return sf::fail(ctx, SF_EINVAL, "%s: n_trees %u outside 1..65535", who, m.n_trees);
+    if (m.n_features < 1 || m.n_features > SF_MAX_FEATURES)
+        return sf::fail(ctx, SF_EINVAL, "%s: n_features %u outside 1..%d", who, m.n_features, SF_MAX_FEATURES);
+    if (!m.node_feat || !m.node_thr) return sf::fail(ctx, SF_EINVAL, "%s: model arrays missing", who);
+    return SF_OK;
+}
 
 // every entry point of this file: n_flows rows (all flows, or the capacity of the list idx)
 int run_trees(sf_ctx* ctx, const char* who, const float* feat, uint32_t feat_ld, uint32_t n_flows, const uint32_t* idx,
@@ -395,19 +417,17 @@ int run_trees(sf_ctx* ctx, const char* who, const float* feat, uint32_t feat_ld,
     if (!feat || !out.pred || (gbdt ? !out.score : !out.top_votes))
         return sf::fail(ctx, SF_EINVAL, "%s: feat, pred or %s is NULL", who, gbdt ? "score" : "top_votes");
 
-    sf::Carve ws(ctx);
-    const size_t pack_bytes = sf::forest_pack_bytes(m.n_trees, m.depth);
-    PairRec* packed = (PairRec*)ws.take(pack_bytes);
-    if (!packed)
-        return sf::fail(ctx, SF_ENOMEM, "%s: workspace has %zu bytes, packed trees need %zu", who, ctx->ws_bytes,
-                        pack_bytes + sf::kFlagBytes);
-    {
-        const uint64_t total = (uint64_t)m.n_trees * recs_upto(pair_levels(m.depth));
-        uint64_t blocks = (total + 255) / 256;
-        if (blocks > 8192) blocks = 8192;
-        pack_forest<<<(uint32_t)blocks, 256, 0, ctx->stream>>>(m.n_trees, m.depth, m.n_features, m.node_feat, m.node_thr,
-                                                               packed);
-        SF_LAUNCH_CHECK(ctx, "pack_forest");
+    const PairRec* packed = (const PairRec*)m.packed;
+    if (!packed) {
+        sf::Carve ws(ctx);
+        const size_t pack_bytes = sf::forest_pack_bytes(m.n_trees, m.depth);
+        PairRec* mine = (PairRec*)ws.take(pack_bytes);
+        if (!mine)
+            return sf::fail(ctx, SF_ENOMEM, "%s: workspace has %zu bytes, packed trees need %zu", who, ctx->ws_bytes,
+                            pack_bytes + sf::kFlagBytes);
+        const int rc = pack_into(ctx, m, mine);
+        if (rc != SF_OK) return rc;
+        packed = mine;
     }
     FastArgs a;
     a.feat = feat;
@@ -479,7 +499,7 @@ int run_forest(sf_ctx* ctx, const char* who, const float* feat, uint32_t feat_ld
 {
     if (!f) return sf::fail(ctx, SF_EINVAL, "%s: forest is NULL", who);
     const TreeModel m = {f->n_trees, f->depth, f->n_classes, f->n_features, f->node_feat, f->node_thr, f->leaf_label,
-                         nullptr, nullptr};
+                         nullptr, nullptr, f->packed};
     const Outputs out = {votes, pred, top_votes, leaf_idx, labels, nullptr, nullptr, 0};
     return run_trees(ctx, who, feat, feat_ld, n_flows, idx, idx_count, n_rows, m, false, out);
 }
@@ -515,7 +535,31 @@ extern "C" int sf_gbdt_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, u
     if (score_kind != SF_SCORE_LC && score_kind != SF_SCORE_ENTROPY)
         return sf::fail(ctx, SF_EINVAL, "sf_gbdt_infer: score_kind %d is neither SF_SCORE_LC nor SF_SCORE_ENTROPY", score_kind);
     const TreeModel m = {model->n_trees, model->depth, model->n_classes, model->n_features, model->node_feat,
-                         model->node_thr, nullptr, model->leaf_value, model->base};
+                         model->node_thr, nullptr, model->leaf_value, model->base, model->packed};
     const Outputs out = {nullptr, pred, nullptr, leaf_idx, nullptr, margins, score, score_kind};
     return run_trees(ctx, "sf_gbdt_infer", feat, feat_ld, n_flows, nullptr, nullptr, n_flows, m, true, out);
+}
+
+extern "C" size_t sf_forest_packed_bytes(uint32_t n_trees, uint32_t depth) { return sf::forest_pack_bytes(n_trees, depth); }
+
+extern "C" int sf_forest_pack(sf_ctx* ctx, const sf_forest* f, void* packed)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_forest_pack: ctx is NULL");
+    if (!f || !packed) return sf::fail(ctx, SF_EINVAL, "sf_forest_pack: forest or packed is NULL");
+    if ((uintptr_t)packed & 15u) return sf::fail(ctx, SF_EINVAL, "sf_forest_pack: packed is not 16-byte aligned");
+    const TreeModel m = {f->n_trees, f->depth, f->n_classes, f->n_features, f->node_feat, f->node_thr, f->leaf_label,
+                         nullptr, nullptr, nullptr};
+    const int rc = check_model(ctx, "sf_forest_pack", m);
+    return rc != SF_OK ? rc : pack_into(ctx, m, (PairRec*)packed);
+}
+
+extern "C" int sf_gbdt_pack(sf_ctx* ctx, const sf_gbdt* g, void* packed)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_gbdt_pack: ctx is NULL");
+    if (!g || !packed) return sf::fail(ctx, SF_EINVAL, "sf_gbdt_pack: model or packed is NULL");
+    if ((uintptr_t)packed & 15u) return sf::fail(ctx, SF_EINVAL, "sf_gbdt_pack: packed is not 16-byte aligned");
+    const TreeModel m = {g->n_trees, g->depth, g->n_classes, g->n_features, g->node_feat, g->node_thr, nullptr,
+                         g->leaf_value, g->base, nullptr};
+    const int rc = check_model(ctx, "sf_gbdt_pack", m);
+    return rc != SF_OK ? rc : pack_into(ctx, m, (PairRec*)packed);
 }

@@ -19,9 +19,10 @@
 namespace sf {
 bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
 size_t slow_fused_ws_bytes(const sf_mlp* mlp);
-int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint32_t n_rows, const uint32_t* esc_idx,
-               const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_labels, const sf_mlp* mlp,
-               float* logits, uint16_t* labels);
+int slow_fused(sf_ctx* ctx, void* ws, bool ws_is_ordered, const float* feat, uint32_t feat_ld, uint32_t n_rows,
+               const uint32_t* esc_idx, const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap,
+               uint32_t n_labels, const sf_mlp* mlp, float* logits, uint16_t* labels);
+int order_all(sf_ctx* ctx, const sf_mlp* mlp, void* out);
 } // namespace sf
 
 namespace {
@@ -498,11 +499,10 @@ int reorder_weights_async(sf_ctx* ctx, const ReorderSpec* specs, int n_specs)
     return SF_OK;
 }
 
-int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint32_t n_rows, const uint32_t* esc_idx,
-               const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_labels, const sf_mlp* m,
-               float* logits, uint16_t* labels)
+// w1 | w2 | w3 in operand order, at the offsets every consumer uses (the last layer padded to 32 columns)
+int order_all(sf_ctx* ctx, const sf_mlp* m, void* out)
 {
-    char* p = (char*)ws;
+    char* p = (char*)out;
     uint4* w1s = (uint4*)p;
     p += sw_bytes(m->n_h1, m->n_in);
     uint4* w2s = (uint4*)p;
@@ -510,8 +510,21 @@ int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint3
     uint4* w3s = (uint4*)p;
     const ReorderSpec specs[3] = {{m->w1, m->n_h1, m->n_in, w1s}, {m->w2, m->n_h2, m->n_h1, w2s},
                                   {m->w3, m->n_classes, m->n_h2, w3s}};
-    {
-        const int rc = reorder_weights_async(ctx, specs, 3);
+    return reorder_weights_async(ctx, specs, 3);
+}
+
+int slow_fused(sf_ctx* ctx, void* ws, bool ws_is_ordered, const float* feat, uint32_t feat_ld, uint32_t n_rows,
+               const uint32_t* esc_idx, const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap,
+               uint32_t n_labels, const sf_mlp* m, float* logits, uint16_t* labels)
+{
+    char* p = (char*)ws;
+    uint4* w1s = (uint4*)p;
+    p += sw_bytes(m->n_h1, m->n_in);
+    uint4* w2s = (uint4*)p;
+    p += sw_bytes(m->n_h2, m->n_h1);
+    uint4* w3s = (uint4*)p;
+    if (!ws_is_ordered) {
+        const int rc = order_all(ctx, m, ws);
         if (rc != SF_OK) return rc;
     }
     FusedArgs a;

@@ -17,9 +17,10 @@ namespace sf {
 // fused single-kernel form for narrow hidden layers (slow_fused.hip)
 bool slow_fused_ok(const sf_mlp* mlp, bool raw_input);
 size_t slow_fused_ws_bytes(const sf_mlp* mlp);
-int slow_fused(sf_ctx* ctx, void* ws, const float* feat, uint32_t feat_ld, uint32_t n_rows, const uint32_t* esc_idx,
-               const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap, uint32_t n_labels, const sf_mlp* mlp,
-               float* logits, uint16_t* labels);
+int slow_fused(sf_ctx* ctx, void* ws, bool ws_is_ordered, const float* feat, uint32_t feat_ld, uint32_t n_rows,
+               const uint32_t* esc_idx, const uint32_t* scatter, const uint32_t* esc_count, uint32_t esc_cap,
+               uint32_t n_labels, const sf_mlp* mlp, float* logits, uint16_t* labels);
+int order_all(sf_ctx* ctx, const sf_mlp* mlp, void* out);
 // one hidden layer of any width on operand-ordered weights (slow_wide.hip)
 int wide_layer(sf_ctx* ctx, int amode, const sfmlp::LayerArgs& a, const void* w_ordered, uint32_t rows_cap);
 } // namespace sf
@@ -378,22 +379,31 @@ int run_slow(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows, 
     }
 
     sf::Carve ws(ctx);
+    const bool bf = mlp->dtype == SF_BF16;
     if (sf::slow_fused_ok(mlp, raw_src != nullptr)) {
+        if (mlp->ordered)
+            return sf::slow_fused(ctx, const_cast<void*>(mlp->ordered), true, feat, feat_ld, n_rows, esc_idx, scatter, esc_count,
+                                  esc_cap, n_flows, mlp, logits, labels);
         const size_t need = sf::slow_fused_ws_bytes(mlp);
         void* w = ws.take(need);
         if (!w) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace too small for %zu bytes of re-ordered weights", need);
-        return sf::slow_fused(ctx, w, feat, feat_ld, n_rows, esc_idx, scatter, esc_count, esc_cap, n_flows, mlp, logits, labels);
+        return sf::slow_fused(ctx, w, false, feat, feat_ld, n_rows, esc_idx, scatter, esc_count, esc_cap, n_flows, mlp, logits,
+                              labels);
     }
-    const bool bf = mlp->dtype == SF_BF16;
-    void *w1o = nullptr, *w2o = nullptr;
-    if (bf) {
+    const void *w1o = nullptr, *w2o = nullptr;
+    if (bf && mlp->ordered) {
+        w1o = mlp->ordered;
+        w2o = (const char*)mlp->ordered + sf::reordered_bytes(mlp->n_h1, mlp->n_in);
+    } else if (bf) {
         // operand-ordered copies of the two hidden layers' weights
-        w1o = ws.take(sf::reordered_bytes(mlp->n_h1, mlp->n_in));
-        w2o = ws.take(sf::reordered_bytes(mlp->n_h2, mlp->n_h1));
-        if (!w1o || !w2o) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace too small for the re-ordered weights");
-        const sf::ReorderSpec specs[2] = {{mlp->w1, mlp->n_h1, mlp->n_in, w1o}, {mlp->w2, mlp->n_h2, mlp->n_h1, w2o}};
+        void* o1 = ws.take(sf::reordered_bytes(mlp->n_h1, mlp->n_in));
+        void* o2 = ws.take(sf::reordered_bytes(mlp->n_h2, mlp->n_h1));
+        if (!o1 || !o2) return sf::fail(ctx, SF_ENOMEM, "sf_slow_infer: workspace too small for the re-ordered weights");
+        const sf::ReorderSpec specs[2] = {{mlp->w1, mlp->n_h1, mlp->n_in, o1}, {mlp->w2, mlp->n_h2, mlp->n_h1, o2}};
         const int rc = sf::reorder_weights_async(ctx, specs, 2);
         if (rc != SF_OK) return rc;
+        w1o = o1;
+        w2o = o2;
     }
     const uint32_t ld1 = bf ? pad64(mlp->n_h1) : mlp->n_h1, ld2 = bf ? pad64(mlp->n_h2) : mlp->n_h2;
     const size_t row_bytes = bf ? ((size_t)ld1 + ld2) * 2 : ((size_t)mlp->n_in + ld1 + ld2 + mlp->n_classes) * 4;
@@ -540,4 +550,22 @@ extern "C" int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat
     if (pair_cap && n_flows && n_rows && !pair_flow) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer_pairs: pair_flow is NULL");
     return run_slow(ctx, feat, feat_ld, n_rows, nullptr, nullptr, pair_row, pair_flow, n_pairs, pair_cap, n_flows, mlp,
                     nullptr, logits, labels);
+}
+
+extern "C" size_t sf_mlp_ordered_bytes(const sf_mlp* mlp)
+{
+    if (!mlp || mlp->dtype != SF_BF16 || !mlp->n_in || !mlp->n_h1 || !mlp->n_h2 || !mlp->n_classes) return 0;
+    return sf::reordered_bytes(mlp->n_h1, mlp->n_in) + sf::reordered_bytes(mlp->n_h2, mlp->n_h1) +
+           sf::reordered_bytes(32, mlp->n_h2);
+}
+
+extern "C" int sf_mlp_order(sf_ctx* ctx, const sf_mlp* mlp, void* ordered)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_mlp_order: ctx is NULL");
+    if (!mlp || !ordered) return sf::fail(ctx, SF_EINVAL, "sf_mlp_order: mlp or ordered is NULL");
+    if (mlp->dtype != SF_BF16) return sf::fail(ctx, SF_EINVAL, "sf_mlp_order: only bfloat16 models have an ordered copy");
+    if (!mlp->n_in || !mlp->n_h1 || !mlp->n_h2 || !mlp->n_classes || mlp->n_classes > 32 || !mlp->w1 || !mlp->w2 || !mlp->w3)
+        return sf::fail(ctx, SF_EINVAL, "sf_mlp_order: widths, class count (at most 32) or weights missing");
+    if ((uintptr_t)ordered & 255u) return sf::fail(ctx, SF_EINVAL, "sf_mlp_order: ordered is not 256-byte aligned");
+    return sf::order_all(ctx, mlp, ordered);
 }

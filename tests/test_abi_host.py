@@ -44,13 +44,13 @@ def test_struct_layouts_match_header(tmp_path):
                                            "pkt_hdr", "hdr_words"]),
               "sf_feat_cfg": (b.SfFeatCfg, ["n_windows", "depth", "raw_pkts", "raw_bits"]),
               "sf_forest": (b.SfForest, ["n_trees", "depth", "n_classes", "n_features", "node_feat", "node_thr",
-                                         "leaf_label"]),
+                                         "leaf_label", "packed"]),
               "sf_tree": (b.SfTree, ["depth", "n_classes", "n_features", "node_feat", "node_thr", "leaf_count"]),
               "sf_gbdt": (b.SfGbdt, ["n_trees", "depth", "n_classes", "n_features", "node_feat", "node_thr",
-                                     "leaf_value", "base"]),
+                                     "leaf_value", "base", "packed"]),
               "sf_join_table": (b.SfJoinTable, ["slots", "cap_log2"]),
               "sf_mlp": (b.SfMlp, ["n_in", "n_h1", "n_h2", "n_classes", "dtype", "mu", "inv_sigma", "clamp",
-                                   "w1", "w2", "w3", "b1", "b2", "b3"])}
+                                   "w1", "w2", "w3", "b1", "b2", "b3", "ordered"])}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "serveflow.h"', 'int main(void){']
     for name, (_, fs) in fields.items():
         lines.append('printf("%s %%zu\\n", sizeof(%s));' % (name, name))

@@ -34,6 +34,8 @@ def _full(cfg_id, n, vmin, logit_sample):
     esc_count = torch.zeros(1, dtype=torch.int32, device=dev)
     labels = torch.empty(n, dtype=torch.int16, device=dev)
     logits = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
+    ctx.sf_forest_pack(d_forest)        # models laid out once, as in the benchmark
+    ctx.sf_mlp_order(d_mlp)
     for _ in range(2):          # twice: the second pass runs on a warm workspace, as in the benchmark
         ctx.sf_featurize(d_pk, cfg.depths, feat)
         ctx.sf_fast_infer(feat, d_forest, pred, top)
@@ -113,6 +115,8 @@ def test_three_tier_full_size():
     cnt1 = torch.zeros(1, dtype=torch.int32, device=dev)
     cnt2 = torch.zeros(1, dtype=torch.int32, device=dev)
     logits = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
+    ctx.sf_forest_pack(d_forest)
+    ctx.sf_mlp_order(d_mlp)
     for _ in range(2):
         ctx.sf_featurize(d_pk, cfg.depths, feat)
         ctx.sf_fastest_infer(feat, d_tree, labels, top0, tot0)
