@@ -32,10 +32,10 @@ GATHER_BOUND_VISITS_PER_S = 64.0 / (5.0 + 9.5 / 2.0) * 256 * 2.4e9
 # WRITE_SIZE scaled by a 256 MiB reference copy (profiles/cfg2_1m_hbm_traffic.txt).  Each entry is tied to
 # the kernel source it was measured on: once that file changes, the figure is reported as null again.
 MEASURED_TRAFFIC = {
-    "sf_featurize": ("featurize.hip", "f0e5fb7c57c0930d", 392450991),
-    "sf_fast_infer": ("fast_infer.hip", "0799fd54eb50e763", 374984108),
+    "sf_featurize": ("featurize.hip", "f0e5fb7c57c0930d", 392450735),
+    "sf_fast_infer": ("fast_infer.hip", "3dc4506a0bcc4e33", 375499309),
     "sf_route": ("route.hip", "f58da4221819e5b2", 5108834),
-    "sf_slow_infer": ("slow_fused.hip", "080ae2c67eb6d8aa", 54119509),
+    "sf_slow_infer": ("slow_fused.hip", "7070d6a31c27f659", 54118997),
 }
 
 
