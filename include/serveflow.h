@@ -6,6 +6,9 @@
  * first k packets and classified by a fast tree ensemble; an uncertainty score decides
  * which flows are certain enough (Section 3.2); the uncertain ones are compacted into a
  * list and re-classified by a slower dense model, whose label replaces the fast one.
+ * Around these four steps: a decision tree as a tier in front (the three-tier cascade of
+ * Section 3.1), gradient-boosted trees as the fast model with the entropy score, the threshold
+ * algorithms of Section 3.2, and the flow-ID join of the two queues in front of the slow model.
  *
  * Conventions that hold for every entry point
  *   - Pointers inside the structs and pointer arguments are DEVICE pointers unless the
