@@ -144,7 +144,8 @@ int sf_forest_pack(sf_ctx* ctx, const sf_forest* forest, void* packed);
 
 /* feat: [n_flows][feat_ld], n_features <= feat_ld.  pred, top_votes: [n_flows].
  * votes: optional [n_flows][n_classes]; leaf_idx: optional [n_flows][n_trees] (for parity
- * checks).  Uses workspace for a packed copy of the forest (8 bytes per node). */
+ * checks).  Uses workspace for a packed copy of the forest (sf_forest_packed_bytes) unless
+ * forest->packed is set. */
 int sf_fast_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_flows,
                   const sf_forest* forest, uint16_t* votes, uint16_t* pred,
                   uint16_t* top_votes, uint16_t* leaf_idx);
