@@ -165,6 +165,18 @@ int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint3
              const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx,
              uint32_t* esc_count);
 
+/* sf_route for callers that cannot allocate device memory or hand over a workspace for this step
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same results, but the per-block counts between its two launches live in a 16 KB array
+ * that is part of the library's device code (one copy per GPU, held until the process ends) instead
+ * of the context's workspace.  The call allocates nothing, on the host or on the device.
+ * At most SF_ROUTE_STATIC_MAX_FLOWS flows per call (SF_EUNSUPPORTED beyond).  Every call on a GPU
+ * uses that GPU's one array, whatever the context or stream: calls that overlap on one GPU race
+ * (calls in stream order are fine; nothing in the array has to be cleared between them). */
+#define SF_ROUTE_STATIC_MAX_FLOWS 2147483648u
+int sf_route_static(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
+                    const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count);
+
 /* ceil(theta * n_trees), exact for theta's binary32 value, clamped to 0..65535.  Host. */
 uint32_t sf_vmin_from_theta(float theta, uint32_t n_trees);
 

@@ -25,7 +25,7 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
            "sf_class_score_histogram", "sf_per_class_thresholds", "sf_join_table_bytes", "sf_join_workspace_bytes",
            "sf_join_step", "sf_join_pending", "sf_slow_infer_pairs", "sf_forest_packed_bytes", "sf_forest_pack",
-           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order")
+           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order", "sf_route_static")
 
 
 class SfPackets(ctypes.Structure):
@@ -104,6 +104,8 @@ def load_library() -> ctypes.CDLL:
     lib.sf_validate_forest.argtypes = [vp, ctypes.POINTER(SfForest)]
     lib.sf_route.restype = ctypes.c_int
     lib.sf_route.argtypes = [vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
+    lib.sf_route_static.restype = ctypes.c_int
+    lib.sf_route_static.argtypes = lib.sf_route.argtypes
     lib.sf_vmin_from_theta.restype = u32
     lib.sf_vmin_from_theta.argtypes = [ctypes.c_float, u32]
     lib.sf_slow_infer.restype = ctypes.c_int
@@ -414,6 +416,14 @@ class ServeFlow:
         n = int(top_votes.shape[0]) if n_flows is None else n_flows
         self._check(self._lib.sf_route(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr, len(vm),
                                        _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_route_static(self, top_votes: torch.Tensor, pred: Optional[torch.Tensor], vmin, esc_idx: torch.Tensor,
+                        esc_count: torch.Tensor, n_flows: Optional[int] = None):
+        vm = [int(vmin)] if isinstance(vmin, int) else [int(v) for v in vmin]
+        arr = (ctypes.c_uint16 * len(vm))(*vm)
+        n = int(top_votes.shape[0]) if n_flows is None else n_flows
+        self._check(self._lib.sf_route_static(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr,
+                                              len(vm), _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
 
     # ---- models prepared once instead of per call ---------------------------------------------
     def _aligned_bytes(self, n: int) -> torch.Tensor:

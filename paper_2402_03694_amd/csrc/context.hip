@@ -45,6 +45,7 @@ size_t slow_row_bytes(uint32_t n_h1, uint32_t n_h2, int dtype)
 
 namespace sf {
 size_t reordered_bytes(uint32_t N, uint32_t K); // slow_fused.hip
+int route_static_init(sf_ctx* ctx);             // route.hip: address of this device's static block counts
 }
 
 extern "C" size_t sf_workspace_bytes(uint32_t max_flows, uint32_t n_trees, uint32_t tree_depth,
@@ -97,6 +98,13 @@ extern "C" int sf_create(sf_ctx** out, void* hip_stream, void* workspace, size_t
     c->n_cu = prop.multiProcessorCount;
     c->d_flags = (uint32_t*)workspace;
     c->err[0] = 0;
+    // set-up for the entry point that uses the static scratch array: look its address up now, once per device
+    const int rs = sf::route_static_init(c);
+    if (rs != SF_OK) {
+        sf::set_global_error("sf_create: %s", c->err);
+        delete c;
+        return rs;
+    }
     *out = c;
     return SF_OK;
 }

@@ -10,6 +10,7 @@
 // pop-counts gives each lane its write position).  The count stays on the device.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -252,15 +253,19 @@ __global__ __launch_bounds__(256) void hist_float_keys(const float* __restrict__
 }
 
 // shared launch of the two kernels; a.top, a.pred, a.total, a.theta, a.src_*, a.n, a.n_vmin and
-// a.vmin are filled by the caller
-int launch_route(sf_ctx* ctx, const char* who, RouteArgs& a, uint32_t* esc_idx, uint32_t* esc_count)
+// a.vmin are filled by the caller.  counts: kMaxBlocks words of device scratch, or NULL to take
+// them from the context's workspace.
+int launch_route(sf_ctx* ctx, const char* who, RouteArgs& a, uint32_t* esc_idx, uint32_t* esc_count,
+                 uint32_t* counts = nullptr)
 {
-    sf::Carve ws(ctx);
-    // workspace contents do not outlive a call: every entry point carves from the start
-    uint32_t* counts = (uint32_t*)ws.take(sf::route_scratch_bytes(a.n));
-    if (!counts)
-        return sf::fail(ctx, SF_ENOMEM, "%s: workspace too small for %zu bytes of block counts", who,
-                        sf::route_scratch_bytes(a.n));
+    if (!counts) {
+        sf::Carve ws(ctx);
+        // workspace contents do not outlive a call: every entry point carves from the start
+        counts = (uint32_t*)ws.take(sf::route_scratch_bytes(a.n));
+        if (!counts)
+            return sf::fail(ctx, SF_ENOMEM, "%s: workspace too small for %zu bytes of block counts", who,
+                            sf::route_scratch_bytes(a.n));
+    }
     uint64_t tiles = ((uint64_t)a.n + kTile - 1) / kTile;
     uint64_t tiles_per_block = (tiles + kMaxBlocks - 1) / kMaxBlocks;
     a.chunk = (uint32_t)(tiles_per_block * kTile);
@@ -291,7 +296,42 @@ int fill_vmin(sf_ctx* ctx, const char* who, RouteArgs& a, const uint16_t* host_v
     return SF_OK;
 }
 
+// ---- block counts for callers that cannot allocate ---------------------------------------------
+// One array per GPU, part of the loaded code object, held until the process ends.  The name is a
+// host-side stand-in for the symbol, not a device address: host code only ever uses the pointer
+// that hipGetSymbolAddress returned for the device at hand.
+static __device__ __align__(256) uint32_t scratch[kMaxBlocks];
+
+constexpr int kMaxDevices = 64;
+uint32_t* g_scratch_ptr[kMaxDevices]; // per device: address of that device's copy of scratch
+std::mutex g_scratch_mu;
+
+// the current device's copy of scratch, looked up once per device with that device current
+int scratch_of_current_device(sf_ctx* ctx, uint32_t** out)
+{
+    int dev = -1;
+    SF_HIP(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return sf::fail(ctx, SF_EUNSUPPORTED, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        uint32_t* p = nullptr;
+        SF_HIP(ctx, hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        if (!p) return sf::fail(ctx, SF_EHIP, "hipGetSymbolAddress returned no address for the static block counts");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SF_OK;
+}
+
 } // namespace
+
+namespace sf {
+int route_static_init(sf_ctx* ctx)
+{
+    uint32_t* p = nullptr;
+    return scratch_of_current_device(ctx, &p);
+}
+} // namespace sf
 
 extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
                         const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count)
@@ -311,6 +351,35 @@ extern "C" int sf_route(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* 
     a.pred = pred;
     a.n = n_flows;
     return launch_route(ctx, "sf_route", a, esc_idx, esc_count);
+}
+
+extern "C" int sf_route_static(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, uint32_t n_flows,
+                               const uint16_t* host_vmin, uint32_t n_vmin, uint32_t* esc_idx, uint32_t* esc_count)
+{
+    if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_route_static: ctx is NULL");
+    RouteArgs a = {};
+    {
+        const int rc = fill_vmin(ctx, "sf_route_static", a, host_vmin, n_vmin);
+        if (rc != SF_OK) return rc;
+    }
+    if (!esc_count) return sf::fail(ctx, SF_EINVAL, "sf_route_static: esc_count is NULL");
+    if (n_flows > SF_ROUTE_STATIC_MAX_FLOWS)
+        return sf::fail(ctx, SF_EUNSUPPORTED, "sf_route_static: %u flows, the static block counts cover at most %u per call",
+                        n_flows, (unsigned)SF_ROUTE_STATIC_MAX_FLOWS);
+    if (n_flows == 0) return zero_count(ctx, esc_count);
+    if (!top_votes || !esc_idx) return sf::fail(ctx, SF_EINVAL, "sf_route_static: top_votes or esc_idx is NULL");
+    if (n_vmin > 1 && !pred) return sf::fail(ctx, SF_EINVAL, "sf_route_static: per-class thresholds need pred");
+    uint32_t* counts = nullptr;
+    {
+        const int rc = scratch_of_current_device(ctx, &counts);
+        if (rc != SF_OK) return rc;
+    }
+    a.top = top_votes;
+    a.pred = pred;
+    a.n = n_flows;
+    // nothing in the counts has to start at zero: route_count writes the entry of every block of this
+    // launch and route_scatter reads only those
+    return launch_route(ctx, "sf_route_static", a, esc_idx, esc_count, counts);
 }
 
 extern "C" int sf_route_ratio(sf_ctx* ctx, const uint16_t* top_count, const uint16_t* leaf_total, uint32_t n_flows,
