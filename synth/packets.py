@@ -55,33 +55,48 @@ def _flow_lengths(cfg: WorkloadConfig, rng: np.random.Generator, n_flows: int) -
     return np.clip(n, 1, cfg.max_pkts).astype(np.uint32)
 
 
-def _header_words(cfg: WorkloadConfig, rng: np.random.Generator, lens: np.ndarray,
-                  hidden: np.ndarray, model_rng: np.random.Generator) -> np.ndarray:
-    """Bernoulli(0.3) header bits; 64 fixed bit positions carry a per-class constant
-    pattern (a stand-in for protocol fields that identify the service)."""
+def _header_words(cfg: WorkloadConfig, seed: int, lens: np.ndarray, hidden: np.ndarray,
+                  model_rng: np.random.Generator) -> np.ndarray:
+    """Bernoulli(0.3) header bits (a 16-bit uniform below 19661, i.e. p = 0.300003); 64 fixed bit
+    positions carry a per-class constant pattern (a stand-in for protocol fields that identify the
+    service).  Packets are drawn in chunks of 32,768, chunk c from its own stream (the data seed's
+    generator jumped c+1 times), so chunks can be drawn by a few threads and the result does not
+    depend on how many."""
     n_bits = cfg.raw_bits
     n_pkts = int(lens.sum())
     fixed_pos = model_rng.choice(n_bits, size=64, replace=False)
-    patterns = (model_rng.random((cfg.n_classes, 64)) < 0.5).astype(np.uint8)
+    patterns = (model_rng.random((cfg.n_classes, 64)) < 0.5)
     pkt_class = np.repeat(hidden, lens)
     words = np.empty((n_pkts, cfg.hdr_words), dtype=np.uint32)
-    chunk = 1 << 18
-    for s in range(0, n_pkts, chunk):
-        e = min(n_pkts, s + chunk)
-        bits = (rng.random((e - s, n_bits), dtype=np.float32) < 0.3).astype(np.uint8)
+    chunk = 1 << 15
+    pad = cfg.hdr_words * 32 - n_bits
+
+    def draw(c: int) -> None:
+        s, e = c * chunk, min(n_pkts, (c + 1) * chunk)
+        rng = np.random.Generator(np.random.PCG64(seed).jumped(c + 1))
+        bits = rng.integers(0, 65536, size=(e - s, n_bits), dtype=np.uint16) < 19661
         bits[:, fixed_pos] = patterns[pkt_class[s:e]]
-        pad = cfg.hdr_words * 32 - n_bits
         if pad:
-            bits = np.concatenate([bits, np.zeros((e - s, pad), np.uint8)], axis=1)
+            bits = np.concatenate([bits, np.zeros((e - s, pad), bool)], axis=1)
         by = np.packbits(bits, axis=1, bitorder="big")       # MSB-first within each byte
         words[s:e] = np.ascontiguousarray(by).view("<u4")
+
+    n_chunks = (n_pkts + chunk - 1) // chunk
+    if n_chunks <= 1:
+        for c in range(n_chunks):
+            draw(c)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(min(8, n_chunks)) as pool:
+            list(pool.map(draw, range(n_chunks)))
     return words
 
 
 def make_packets(cfg: WorkloadConfig, batch: int = 0, n_flows: Optional[int] = None) -> PacketBatch:
     """Draw one batch of flows for ``cfg``.  Batch b of a streaming config uses its own seed."""
     n_flows = cfg.n_flows if n_flows is None else n_flows
-    rng = np.random.Generator(np.random.PCG64(cfg.data_seed * 1000 + batch))
+    seed = cfg.data_seed * 1000 + batch
+    rng = np.random.Generator(np.random.PCG64(seed))
     lens = _flow_lengths(cfg, rng, n_flows)
     flow_off = np.zeros(n_flows + 1, dtype=np.uint32)
     csum = np.cumsum(lens, dtype=np.uint64)
@@ -97,5 +112,5 @@ def make_packets(cfg: WorkloadConfig, batch: int = 0, n_flows: Optional[int] = N
     if cfg.raw_pkts > 0:
         hidden = rng.integers(0, cfg.n_classes, size=n_flows, dtype=np.uint8)
         model_rng = np.random.Generator(np.random.PCG64(cfg.model_seed * 1000 + 7))
-        hdr = _header_words(cfg, rng, lens, hidden, model_rng)
+        hdr = _header_words(cfg, seed, lens, hidden, model_rng)
     return PacketBatch(flow_off, size, iat, direction, hdr, hidden)

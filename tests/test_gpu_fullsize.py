@@ -1,8 +1,15 @@
-"""Parity at the full size of the benchmark workload, in the launch configuration bench.py times:
-1,048,576 flows x 16 packets, 64 features, 100 trees of depth 12, 10 classes, bf16 MLP 64-512-512-10.
-Features, pred, top_votes and the escalation list are compared with the oracle on EVERY flow
-(the oracle runs its outer parallel-for on the host cores); slow-model logits on a fixed-stride
-sample of the escalated flows.  A second case runs one full streaming batch of ragged flows."""
+"""Parity at the full size of every workload, in the launch configuration bench.py times (models laid out
+once, two passes so that the second runs on a warm workspace).  Features, pred, top_votes and the
+escalation list are compared with the oracle on EVERY flow (the oracle runs its outer parallel-for on
+the host cores); slow-model logits on every escalated flow where that takes seconds (the 1M-flow stat
+workload, the streaming batches) and on a fixed-stride sample of at least 65,536 escalated flows where
+it would take hours (4,800-wide header-bit input; 4M flows through a 2048-wide model).
+
+Coverage: config 2 (1,048,576 flows), config 3 (1,048,576 flows, header-bit slow model), config 4
+(eight distinct consecutive batches of 65,536 ragged flows, one model), config 5 (4,194,304 flows at
+each of its three thresholds), the three-tier cascade (1,048,576 flows)."""
+import sys
+
 import numpy as np
 import pytest
 
@@ -10,6 +17,23 @@ import oracle
 import synth
 
 pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    # progress that reaches the terminal even when pytest captures output: a long case is not silent
+    print("[fullsize] " + msg, file=sys.__stderr__, flush=True)
+
+
+def _check_logits(g_logits, g_lab, o_logits, o_lab, flows):
+    """The tolerance of the bf16 slow model: 2e-2 absolute on every logit, equal arg-max wherever the
+    oracle's top-2 margin exceeds 5e-2.  Returns the largest error."""
+    err = np.abs(g_logits - o_logits)
+    assert np.all(np.isfinite(g_logits)) and err.max() <= 2e-2, err.max()
+    srt = np.sort(o_logits, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > 5e-2
+    assert clear.mean() > 0.5
+    assert np.array_equal(g_lab[flows][clear], o_lab[flows][clear])
+    return float(err.max())
 
 
 def _full(cfg_id, n, vmin, logit_sample):
@@ -76,13 +100,206 @@ def _full(cfg_id, n, vmin, logit_sample):
 
 
 def test_headline_workload_full_size():
-    frac, err = _full(2, 1 << 20, 14, 32768)
+    frac, err = _full(2, 1 << 20, 14, 1 << 30)      # logits on every escalated flow
     assert 0.15 < frac < 0.20          # the multinomial closed form gives 17.3 % below 14 of 100 votes
 
 
 def test_streaming_batch_full_size():
-    frac, err = _full(4, 65536, 18, 4096)
+    frac, err = _full(4, 65536, 18, 1 << 30)
     assert 0.15 < frac < 0.27
+
+
+def test_streaming_eight_consecutive_batches():
+    """Config 4 as a stream: eight distinct batches (data seeds ...+batch) through one context and one
+    model (thresholds and input map from batch 0), every integer result on every flow of every batch,
+    logits on every escalated flow."""
+    import torch
+    import paper_2402_03694_amd as sf
+    cfg = synth.get_config(4)
+    n, vmin, dev = cfg.n_flows, cfg.vmin, "cuda:0"
+    thr = oracle.default_threads()
+    pk0 = synth.make_packets(cfg, batch=0)
+    calib, _ = oracle.featurize(pk0.flow_off[:cfg.calib_flows + 1], pk0.pkt_size, pk0.pkt_iat, pk0.pkt_dir, cfg.depths,
+                                n_threads=thr)
+    forest, mlp = synth.make_forest(cfg, calib), synth.make_mlp(cfg, calib)
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, *mlp.dims[:3]))
+    d_forest, d_mlp = sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
+    ctx.sf_forest_pack(d_forest)
+    ctx.sf_mlp_order(d_mlp)
+    feat = torch.empty((n, cfg.n_features), dtype=torch.float32, device=dev)
+    pred = torch.empty(n, dtype=torch.int16, device=dev)
+    top = torch.empty(n, dtype=torch.int16, device=dev)
+    esc_idx = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    esc_count = torch.zeros(1, dtype=torch.int32, device=dev)
+    labels = torch.empty(n, dtype=torch.int16, device=dev)
+    logits = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
+    lens = set()
+    for b in range(8):
+        pk = synth.make_packets(cfg, batch=b)
+        lens.add(pk.n_pkts)
+        o = oracle.classify(pk, cfg.depths, forest, vmin, mlp, n_threads=thr)
+        d_pk = sf.packets_to_device(pk, dev)
+        ctx.sf_featurize(d_pk, cfg.depths, feat)
+        ctx.sf_fast_infer(feat, d_forest, pred, top)
+        ctx.sf_route(top, pred, vmin, esc_idx, esc_count)
+        ctx.sf_slow_infer(d_mlp, esc_idx, esc_count, labels, feat=feat, logits=logits, pred=pred)
+        torch.cuda.synchronize()
+        assert np.array_equal(feat.cpu().numpy().view(np.uint32), o["feat"].view(np.uint32)), b
+        assert np.array_equal(pred.cpu().numpy().view(np.uint16), o["pred"]), b
+        assert np.array_equal(top.cpu().numpy().view(np.uint16), o["top_votes"]), b
+        cnt = int(esc_count.cpu().numpy().view(np.uint32)[0])
+        assert cnt == o["esc_idx"].size, b
+        assert np.array_equal(esc_idx.cpu().numpy().view(np.uint32)[:cnt], o["esc_idx"]), b
+        g_lab = labels.cpu().numpy().view(np.uint16)
+        _check_logits(logits.cpu().numpy()[:cnt], g_lab, o["logits"], o["labels"], o["esc_idx"])
+        kept = np.ones(n, bool)
+        kept[o["esc_idx"]] = False
+        assert np.array_equal(g_lab[kept], o["pred"][kept]), b
+        assert 0.15 < cnt / n < 0.27
+    assert len(lens) == 8          # the batches really differ
+
+
+_CFG5 = {}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _release_cfg5():
+    yield
+    _CFG5.clear()          # 2 GB of host features and as much device memory: not kept for the later test files
+
+
+def _cfg5_state():
+    """Config 5 at 4,194,304 flows: packets, oracle features / votes, and the HIP path's features / votes,
+    made once and shared by the three threshold cases (they differ only from the gate on)."""
+    if _CFG5:
+        return _CFG5
+    import torch
+    import paper_2402_03694_amd as sf
+    cfg = synth.get_config(5)
+    n, dev = cfg.n_flows, "cuda:0"
+    thr = oracle.default_threads()
+    _say("config 5: drawing %d flows" % n)
+    pk = synth.make_packets(cfg)
+    _say("config 5: oracle features")
+    o_feat, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=thr)
+    forest = synth.make_forest(cfg, o_feat[:cfg.calib_flows])
+    mlp = synth.make_mlp(cfg, o_feat[:cfg.calib_flows])
+    _say("config 5: oracle forest (%d trees on %d flows)" % (cfg.n_trees, n))
+    _, o_pred, o_top, _ = oracle.fast_infer(o_feat, forest, want_votes=False, n_threads=thr)
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, *mlp.dims[:3]))
+    d_pk, d_forest, d_mlp = sf.packets_to_device(pk, dev), sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
+    ctx.sf_forest_pack(d_forest)
+    ctx.sf_mlp_order(d_mlp)
+    feat = torch.empty((n, cfg.n_features), dtype=torch.float32, device=dev)
+    pred = torch.empty(n, dtype=torch.int16, device=dev)
+    top = torch.empty(n, dtype=torch.int16, device=dev)
+    for _ in range(2):
+        ctx.sf_featurize(d_pk, cfg.depths, feat)
+        ctx.sf_fast_infer(feat, d_forest, pred, top)
+    torch.cuda.synchronize()
+    _say("config 5: comparing features and votes of every flow")
+    g = feat.cpu().numpy()
+    assert np.array_equal(g.view(np.uint32), o_feat.view(np.uint32)), \
+        "first differing flow %d" % int(np.argwhere(g.view(np.uint32) != o_feat.view(np.uint32))[0, 0])
+    del g
+    assert np.array_equal(pred.cpu().numpy().view(np.uint16), o_pred)
+    assert np.array_equal(top.cpu().numpy().view(np.uint16), o_top)
+    _CFG5.update(cfg=cfg, n=n, thr=thr, o_feat=o_feat, o_pred=o_pred, o_top=o_top, mlp=mlp, ctx=ctx, d_mlp=d_mlp,
+                 feat=feat, pred=pred, top=top)
+    return _CFG5
+
+
+@pytest.mark.parametrize("vmin,lo,hi", [(22, 0.04, 0.075), (23, 0.16, 0.215), (25, 0.55, 0.61)])
+def test_escalation_sweep_full_size(vmin, lo, hi):
+    """Config 5 at one of its three thresholds (5.7 / 18.7 / 58 % escalated by the multinomial closed form): the
+    list on every flow, the 128-2048-2048-32 model over all escalated rows (several workspace chunks), logits
+    on a fixed-stride sample of >= 65,536 of them, final labels of every kept flow."""
+    import torch
+    st = _cfg5_state()
+    cfg, n, ctx, dev = st["cfg"], st["n"], st["ctx"], "cuda:0"
+    o_esc = oracle.route(st["o_top"], st["o_pred"], vmin)
+    assert lo < o_esc.size / n < hi
+    esc_idx = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    esc_count = torch.zeros(1, dtype=torch.int32, device=dev)
+    labels = torch.empty(n, dtype=torch.int16, device=dev)
+    logits = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
+    for _ in range(2):
+        ctx.sf_route(st["top"], st["pred"], vmin, esc_idx, esc_count)
+        ctx.sf_slow_infer(st["d_mlp"], esc_idx, esc_count, labels, feat=st["feat"], logits=logits, pred=st["pred"])
+    torch.cuda.synchronize()
+    cnt = int(esc_count.cpu().numpy().view(np.uint32)[0])
+    assert cnt == o_esc.size
+    g_esc = esc_idx.cpu().numpy().view(np.uint32)[:cnt]
+    assert np.array_equal(g_esc, o_esc)
+    stride = max(1, cnt // 65536)
+    rows = np.arange(0, cnt, stride)
+    assert rows.size >= min(cnt, 65536)
+    _say("config 5, vmin %d: %d escalated (%.1f %%), oracle logits on %d of them" % (vmin, cnt, 100.0 * cnt / n, rows.size))
+    sub = o_esc[rows]
+    o_logits, o_lab = oracle.slow_infer(sub, st["mlp"], n, feat=st["o_feat"], n_threads=st["thr"])
+    g_lab = labels.cpu().numpy().view(np.uint16)
+    g_logits = logits.cpu().numpy()
+    assert np.all(np.isfinite(g_logits[:cnt]))          # every row of every chunk was written
+    _check_logits(g_logits[rows], g_lab, o_logits, o_lab, sub)
+    kept = np.ones(n, bool)
+    kept[o_esc] = False
+    assert np.array_equal(g_lab[kept], st["o_pred"][kept])
+
+
+def test_header_bit_workload_full_size():
+    """Config 3 at 1,048,576 flows: features, votes and the list on every flow; the 4800-1024-512-10 model reads
+    the packed header bits of the escalated flows; logits on a fixed-stride sample of >= 65,536 of them."""
+    import torch
+    import paper_2402_03694_amd as sf
+    cfg = synth.get_config(3)
+    n, vmin, dev = cfg.n_flows, 14, "cuda:0"
+    thr = oracle.default_threads()
+    _say("config 3: drawing %d flows with header bits" % n)
+    pk = synth.make_packets(cfg)
+    o_feat, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=thr)
+    forest = synth.make_forest(cfg, o_feat[:cfg.calib_flows])
+    mlp = synth.make_mlp(cfg, None)
+    _, o_pred, o_top, _ = oracle.fast_infer(o_feat, forest, want_votes=False, n_threads=thr)
+    o_esc = oracle.route(o_top, o_pred, vmin)
+    assert 0.15 < o_esc.size / n < 0.20
+
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, cfg.n_trees, cfg.tree_depth, *mlp.dims[:3]))
+    d_pk, d_forest, d_mlp = sf.packets_to_device(pk, dev), sf.forest_to_device(forest, dev), sf.mlp_to_device(mlp, dev)
+    ctx.sf_forest_pack(d_forest)
+    ctx.sf_mlp_order(d_mlp)
+    feat = torch.empty((n, cfg.n_features), dtype=torch.float32, device=dev)
+    pred = torch.empty(n, dtype=torch.int16, device=dev)
+    top = torch.empty(n, dtype=torch.int16, device=dev)
+    esc_idx = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    esc_count = torch.zeros(1, dtype=torch.int32, device=dev)
+    labels = torch.empty(n, dtype=torch.int16, device=dev)
+    logits = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
+    for _ in range(2):
+        ctx.sf_featurize(d_pk, cfg.depths, feat)
+        ctx.sf_fast_infer(feat, d_forest, pred, top)
+        ctx.sf_route(top, pred, vmin, esc_idx, esc_count)
+        ctx.sf_slow_infer(d_mlp, esc_idx, esc_count, labels, raw_src=d_pk, raw_pkts=cfg.raw_pkts, raw_bits=cfg.raw_bits,
+                          logits=logits, pred=pred)
+    torch.cuda.synchronize()
+    assert np.array_equal(feat.cpu().numpy().view(np.uint32), o_feat.view(np.uint32))
+    assert np.array_equal(pred.cpu().numpy().view(np.uint16), o_pred)
+    assert np.array_equal(top.cpu().numpy().view(np.uint16), o_top)
+    cnt = int(esc_count.cpu().numpy().view(np.uint32)[0])
+    assert cnt == o_esc.size
+    assert np.array_equal(esc_idx.cpu().numpy().view(np.uint32)[:cnt], o_esc)
+    rows = np.arange(0, cnt, max(1, cnt // 65536))
+    assert rows.size >= 65536
+    _say("config 3: %d escalated (%.1f %%), oracle logits on %d of them" % (cnt, 100.0 * cnt / n, rows.size))
+    sub = o_esc[rows]
+    o_logits, o_lab = oracle.slow_infer(sub, mlp, n, flow_off=pk.flow_off, pkt_hdr=pk.pkt_hdr, raw_pkts=cfg.raw_pkts,
+                                        raw_bits=cfg.raw_bits, n_threads=thr)
+    g_lab = labels.cpu().numpy().view(np.uint16)
+    g_logits = logits.cpu().numpy()
+    assert np.all(np.isfinite(g_logits[:cnt]))
+    _check_logits(g_logits[rows], g_lab, o_logits, o_lab, sub)
+    kept = np.ones(n, bool)
+    kept[o_esc] = False
+    assert np.array_equal(g_lab[kept], o_pred[kept])
 
 
 def test_three_tier_full_size():

@@ -161,6 +161,11 @@ def _check_whole_path(n, kind):
     assert ok.all()
     # routing: identical on every flow whose score both sides agree on (all but a handful, if any)
     firm = np.flatnonzero(same)
+    # how many flows sat on a binary32 rounding boundary (the two binary64 scores differ in their last
+    # places and round to neighbouring binary32 values): reported, and bounded
+    import sys
+    print("[gbdt] %d flows, %s score: %d with neighbouring binary32 scores on the two sides"
+          % (n, kind, n - firm.size), file=sys.__stderr__, flush=True)
     assert firm.size >= n - 8
     g_in, o_in = np.zeros(n, bool), np.zeros(n, bool)
     g_in[g_esc], o_in[o_esc] = True, True
