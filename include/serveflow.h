@@ -404,6 +404,19 @@ int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32
                         const uint32_t* pair_row, const uint32_t* pair_flow, const uint32_t* n_pairs,
                         uint32_t pair_cap, uint32_t n_flows, const sf_mlp* mlp, float* logits, uint16_t* labels);
 
+/* ---- measurement aid ---------------------------------------------------------------------------
+ * Not a step of the method.  The walk of the fast model (Section 3.1: it sees every flow, so it sets the
+ * service rate) is bound by gathers, not by memory bandwidth; sf_probe_gather measures what such gathers
+ * cost on the device at hand, so that a benchmark can price the walk against them.  One launch of `blocks`
+ * blocks of 256 lanes; every lane runs eight chains of `iters` dependent gathers.  kind 0: shared memory,
+ * 4 bytes, the lane's own column at a data-dependent row; kind 1: shared memory, 16 bytes at a
+ * data-dependent record; kind 2: global memory through the caches, 16 bytes at a data-dependent record of
+ * `table`.  table: device, 16-byte aligned, 16 << table_log2 bytes (12 <= table_log2 <= 24; kind 2: from 8) of arbitrary
+ * words, read only; sink: device, [blocks * 256] words, written.  *host_wave_gathers (optional) = number
+ * of 64-lane gathers the launch performs; time it with events on the context's stream. */
+int sf_probe_gather(sf_ctx* ctx, int kind, uint32_t table_log2, uint32_t iters, uint32_t blocks,
+                    const void* table, uint32_t* sink, uint64_t* host_wave_gathers);
+
 #ifdef __cplusplus
 }
 #endif

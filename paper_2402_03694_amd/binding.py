@@ -25,7 +25,7 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
            "sf_class_score_histogram", "sf_per_class_thresholds", "sf_join_table_bytes", "sf_join_workspace_bytes",
            "sf_join_step", "sf_join_pending", "sf_slow_infer_pairs", "sf_forest_packed_bytes", "sf_forest_pack",
-           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order", "sf_route_static")
+           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order", "sf_route_static", "sf_probe_gather")
 
 
 class SfPackets(ctypes.Structure):
@@ -106,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     lib.sf_route.argtypes = [vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
     lib.sf_route_static.restype = ctypes.c_int
     lib.sf_route_static.argtypes = lib.sf_route.argtypes
+    lib.sf_probe_gather.restype = ctypes.c_int
+    lib.sf_probe_gather.argtypes = [vp, ctypes.c_int, u32, u32, u32, vp, vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.sf_vmin_from_theta.restype = u32
     lib.sf_vmin_from_theta.argtypes = [ctypes.c_float, u32]
     lib.sf_slow_infer.restype = ctypes.c_int
@@ -424,6 +426,17 @@ class ServeFlow:
         n = int(top_votes.shape[0]) if n_flows is None else n_flows
         self._check(self._lib.sf_route_static(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr,
                                               len(vm), _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_probe_gather(self, kind: int, table: torch.Tensor, sink: torch.Tensor, iters: int, blocks: int) -> int:
+        """Enqueues one probe launch; returns the number of 64-lane gathers it performs."""
+        words = int(table.numel()) * table.element_size() // 16
+        log2 = words.bit_length() - 1
+        if words != 1 << log2:
+            raise ServeFlowError(SF_EINVAL, "probe table must hold a power of two of 16-byte records")
+        done = ctypes.c_uint64()
+        self._check(self._lib.sf_probe_gather(self._h, int(kind), log2, int(iters), int(blocks), _ptr(table),
+                                              _ptr(sink, torch.int32), ctypes.byref(done)))
+        return int(done.value)
 
     # ---- models prepared once instead of per call ---------------------------------------------
     def _aligned_bytes(self, n: int) -> torch.Tensor:

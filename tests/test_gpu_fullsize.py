@@ -36,7 +36,9 @@ def _check_logits(g_logits, g_lab, o_logits, o_lab, flows):
     return float(err.max())
 
 
-def _full(cfg_id, n, vmin, logit_sample):
+def _full(cfg_id, n, vmin, logit_sample, per_class_target=None):
+    """vmin: the universal threshold; or, with per_class_target, ignored: the thresholds then come from
+    Algorithm 2 on synthetic validation labels, computed by the oracle and, separately, by the library."""
     import torch
     import paper_2402_03694_amd as sf
     cfg = synth.get_config(cfg_id)
@@ -46,6 +48,12 @@ def _full(cfg_id, n, vmin, logit_sample):
     forest = synth.make_forest(cfg, o_feat[:cfg.calib_flows])
     mlp = synth.make_mlp(cfg, o_feat[:cfg.calib_flows])
     _, o_pred, o_top, _ = oracle.fast_infer(o_feat, forest, want_votes=False, n_threads=thr)
+    if per_class_target is not None:
+        truth = synth.make_truth(cfg, o_pred, o_top)
+        o_vmin, o_reached, _ = oracle.per_class_thresholds(o_pred, o_top, truth == o_pred, cfg.n_trees, cfg.n_classes,
+                                                           per_class_target)
+        vmin = [int(v) for v in o_vmin]
+        assert len(set(vmin)) > 1          # the classes really get different thresholds
     o_esc = oracle.route(o_top, o_pred, vmin)
 
     dev = "cuda:0"
@@ -60,6 +68,15 @@ def _full(cfg_id, n, vmin, logit_sample):
     logits = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
     ctx.sf_forest_pack(d_forest)        # models laid out once, as in the benchmark
     ctx.sf_mlp_order(d_mlp)
+    if per_class_target is not None:
+        # the library's own calibration, as the benchmark runs it, must arrive at the oracle's thresholds
+        ctx.sf_featurize(d_pk, cfg.depths, feat)
+        ctx.sf_fast_infer(feat, d_forest, pred, top)
+        d_truth = torch.from_numpy(truth.view(np.int16)).to(dev)
+        hist = ctx.sf_class_score_histogram(top, pred, d_truth, cfg.n_trees, cfg.n_classes)
+        g_vmin, g_reached = sf.sf_per_class_thresholds(hist, cfg.n_trees, cfg.n_classes, per_class_target)
+        assert g_vmin == vmin and abs(g_reached - o_reached) < 1e-12
+        vmin = g_vmin
     for _ in range(2):          # twice: the second pass runs on a warm workspace, as in the benchmark
         ctx.sf_featurize(d_pk, cfg.depths, feat)
         ctx.sf_fast_infer(feat, d_forest, pred, top)
@@ -79,7 +96,8 @@ def _full(cfg_id, n, vmin, logit_sample):
     assert np.array_equal(g_esc, o_esc)
     # properties that hold at any size: ascending, exactly the flows below the threshold
     assert np.all(np.diff(g_esc.astype(np.int64)) > 0)
-    assert np.array_equal(g_esc, np.flatnonzero(o_top < vmin).astype(np.uint32))
+    assert np.array_equal(g_esc, np.flatnonzero(o_top < np.atleast_1d(np.asarray(vmin, np.uint16))[o_pred if per_class_target else 0])
+                          .astype(np.uint32))
 
     stride = max(1, cnt // logit_sample)
     rows = np.arange(0, cnt, stride)
@@ -102,6 +120,13 @@ def _full(cfg_id, n, vmin, logit_sample):
 def test_headline_workload_full_size():
     frac, err = _full(2, 1 << 20, 14, 1 << 30)      # logits on every escalated flow
     assert 0.15 < frac < 0.20          # the multinomial closed form gives 17.3 % below 14 of 100 votes
+
+
+def test_headline_workload_per_class_gate_full_size():
+    """The launch configuration bench.py times by default: per-class thresholds from Algorithm 2 at a target
+    portion of 25 % (which one threshold for all classes cannot reach on an integer score)."""
+    frac, err = _full(2, 1 << 20, None, 65536, per_class_target=0.25)
+    assert 0.24 < frac < 0.26
 
 
 def test_streaming_batch_full_size():
