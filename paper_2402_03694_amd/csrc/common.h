@@ -18,6 +18,7 @@ struct sf_ctx {
     int device;
     int n_cu;          // compute units of the device
     uint32_t* d_flags; // 64 words at the head of the workspace: validation counters etc.
+    uint64_t lds_ready; // bit per kernel (sf::LdsSlot): its dynamic shared-memory limit has been raised
     char err[512];
 };
 
@@ -59,6 +60,20 @@ struct Carve {
         if (e_ != hipSuccess)                                                                \
             return sf::fail((ctx), SF_EHIP, "launch of %s failed: %s", (what),               \
                             hipGetErrorString(e_));                                          \
+    } while (0)
+
+// Kernels that take more dynamic shared memory than the default limit have the limit raised to the
+// whole of a compute unit's, once per context and kernel (the context remembers which).
+constexpr int kLdsLimitBytes = 160 * 1024;
+enum LdsSlot { kLdsForest = 0 /* 12 variants */, kLdsTreeWalk = 12, kLdsWide = 13 /* 3 operand modes */, kLdsFused = 16,
+               kLdsClassify = 17 /* 6 variants */ };
+#define SF_ALLOW_LDS(ctx, slot, func)                                                                         \
+    do {                                                                                                      \
+        if (!((ctx)->lds_ready & (1ull << (slot)))) {                                                         \
+            SF_HIP((ctx), hipFuncSetAttribute((const void*)(func), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                              sf::kLdsLimitBytes));                                           \
+            (ctx)->lds_ready |= 1ull << (slot);                                                               \
+        }                                                                                                     \
     } while (0)
 
 // Bytes each step needs from the workspace (also used by sf_workspace_bytes).

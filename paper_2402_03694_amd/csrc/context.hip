@@ -97,6 +97,7 @@ extern "C" int sf_create(sf_ctx** out, void* hip_stream, void* workspace, size_t
     c->device = dev;
     c->n_cu = prop.multiProcessorCount;
     c->d_flags = (uint32_t*)workspace;
+    c->lds_ready = 0;
     c->err[0] = 0;
     // set-up for the entry point that uses the static scratch array: look its address up now, once per device
     const int rs = sf::route_static_init(c);

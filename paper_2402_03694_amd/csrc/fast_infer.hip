@@ -331,13 +331,12 @@ int launch_votes(sf_ctx* ctx, const FastArgs& a, size_t lds)
 {
     const uint32_t fpb = BS / S;
     const uint32_t grid = (a.n_flows + fpb - 1) / fpb;
+    constexpr int slot = sf::kLdsForest + (S == 1 ? 0 : (S == 2 ? 1 : 2)) * 4 + (GBDT ? 1 : 0);
     if (a.leaf_idx) {
-        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, true, GBDT>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        SF_ALLOW_LDS(ctx, slot + 2, (forest_votes<BS, S, true, GBDT>));
         forest_votes<BS, S, true, GBDT><<<grid, BS, lds, ctx->stream>>>(a);
     } else {
-        SF_HIP(ctx, hipFuncSetAttribute((const void*)forest_votes<BS, S, false, GBDT>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        SF_ALLOW_LDS(ctx, slot, (forest_votes<BS, S, false, GBDT>));
         forest_votes<BS, S, false, GBDT><<<grid, BS, lds, ctx->stream>>>(a);
     }
     SF_LAUNCH_CHECK(ctx, "forest_votes");

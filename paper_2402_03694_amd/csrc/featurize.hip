@@ -27,6 +27,7 @@ struct FeatArgs {
     uint32_t depth[SF_MAX_WINDOWS];
     float* feat;
     uint32_t ld;
+    uint32_t wide_ok; // the packet arrays start on 16-byte (size, time) and 8-byte (direction) boundaries
 };
 
 // float -> unsigned key with the same order (negative values: all bits flipped, others: sign set)
@@ -189,8 +190,8 @@ __global__ __launch_bounds__(kWave) void featurize_wave(FeatArgs a)
     const int avail = (int)(n < dmax ? n : dmax);
     float s[KMAX], t[KMAX];
     uint64_t dmask = 0;
-    if (avail == KMAX && (o & 7u) == 0) {
-        // whole window present and 16-byte aligned: wide loads
+    if (avail == KMAX && (o & 7u) == 0 && a.wide_ok) {
+        // whole window present and 16-byte aligned (array bases included): wide loads
 #pragma unroll
         for (int c = 0; c < KMAX / 8; ++c) {
             const uint4 sz = *reinterpret_cast<const uint4*>(a.size + o + 8 * c);
@@ -317,6 +318,7 @@ extern "C" int sf_featurize(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg
     for (int w = 0; w < SF_MAX_WINDOWS; ++w) a.depth[w] = w < (int)cfg->n_windows ? cfg->depth[w] : 0;
     a.feat = feat;
     a.ld = feat_ld;
+    a.wide_ok = (((uintptr_t)a.size | (uintptr_t)a.iat) & 15u) == 0 && ((uintptr_t)a.dir & 7u) == 0;
     const uint32_t dmax = cfg->depth[cfg->n_windows - 1];
     const uint32_t grid = (a.n_flows + kWave - 1) / kWave;
     if (dmax <= 8)

@@ -131,18 +131,6 @@ static __device__ __forceinline__ uint4 load_a_chunk(const LayerArgs& a, bool ro
     return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
 }
 
-static __device__ __forceinline__ uint4 load_w_chunk(const LayerArgs& a, uint32_t n, uint32_t k)
-{
-    if (n >= a.N || k >= a.K) return make_uint4(0, 0, 0, 0);
-    const uint16_t* p = a.w + (size_t)n * a.K + k;
-    if (k + 8 <= a.K && (a.K & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.w) & 15u) == 0)
-        return *reinterpret_cast<const uint4*>(p);
-    uint16_t v[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = k + q < a.K ? p[q] : (uint16_t)0;
-    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-}
-
 static __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u)
 {
     union {

@@ -187,13 +187,16 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
     }
 }
 
-// H[row][col] = bfloat16(relu(acc)) for the wave's columns (the bias is already in acc).  Columns in
-// [n_valid, n_pad) come out as zeros by themselves: their weights and their bias entries are zero.
+// H[row][col] = bfloat16(relu(acc)) for the wave's columns (the bias is already in acc).  Padding columns
+// [n_valid, n_pad) inside the last real 32-column block come out as zeros by themselves (their weights and
+// bias entries are zero); a column block past the last real one (nb_total) holds a repeat of that block's
+// results in acc and is stored as zeros.
 __device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], uint32_t n0, uint32_t n_pad,
-                                             uint32_t lane)
+                                             uint32_t nb_total, uint32_t lane)
 {
 #pragma unroll
     for (int j = 0; j < kNI; ++j) {
+        const bool real = n0 / 32u + j < nb_total;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5); // first of 4 consecutive columns
@@ -203,7 +206,8 @@ __device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kM
                     const uint32_t row = i * 32u + (lane & 31u);
                     const float y0 = fmaxf(acc[i][j][4 * g + 0], 0.f), y1 = fmaxf(acc[i][j][4 * g + 1], 0.f);
                     const float y2 = fmaxf(acc[i][j][4 * g + 2], 0.f), y3 = fmaxf(acc[i][j][4 * g + 3], 0.f);
-                    *reinterpret_cast<uint2*>(H + row * LDH + col) = make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3));
+                    *reinterpret_cast<uint2*>(H + row * LDH + col) =
+                        real ? make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3)) : make_uint2(0u, 0u);
                 }
             }
         }
@@ -366,13 +370,13 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
         wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc);
         __syncthreads(); // every wave has read the input tile; H may be overwritten
         if (tid < FBM) flow_next[tid] = nf;
-        store_hidden(H, acc, n0, k2p, lane);
+        store_hidden(H, acc, n0, k2p, nb1, lane);
         __syncthreads();
         // layer 2
         bias_acc(acc, s_b2, n0, lane);
         wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc);
         __syncthreads();
-        store_hidden(H, acc, n0, k3p, lane);
+        store_hidden(H, acc, n0, k3p, nb2, lane);
         // layer 3: wave = (row block rb, half kh of K).  The hidden accumulators are dead, so a
         // whole half-layer of weight operands fits in registers; they are requested before the
         // barrier so that their latency overlaps it.
@@ -551,7 +555,7 @@ int slow_fused(sf_ctx* ctx, void* ws, bool ws_is_ordered, const float* feat, uin
     a.b3 = m->b3;
     a.logits = logits;
     a.labels = labels;
-    SF_HIP(ctx, hipFuncSetAttribute((const void*)mlp_fused, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds));
+    SF_ALLOW_LDS(ctx, sf::kLdsFused, mlp_fused);
     uint32_t tiles_cap = (esc_cap + FBM - 1) / FBM;
     uint32_t grid = (uint32_t)ctx->n_cu; // one block per compute unit (its shared memory fills the unit)
     if (grid > tiles_cap) grid = tiles_cap;

@@ -29,18 +29,30 @@ namespace {
 
 using namespace sfmlp;
 
-// One layer.  BN = columns per block; FINAL = last layer (logits, arg-max, label scatter).
-template <int AMODE, int BN, bool FINAL>
-__global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
+// 8 consecutive K values [k, k+8) of weight row n (row-major [N][K] bfloat16 bits), zero outside
+__device__ __forceinline__ uint4 load_w_chunk(const LayerArgs& a, uint32_t n, uint32_t k)
 {
-    constexpr int WAVES_N = BN >= 128 ? 2 : 1;
-    constexpr int WAVES_M = 4 / WAVES_N;
-    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N; // wave tile
-    constexpr int MI = WM / 32, NI = WN / 32;
+    if (n >= a.N || k >= a.K) return make_uint4(0, 0, 0, 0);
+    const uint16_t* p = a.w + (size_t)n * a.K + k;
+    if (k + 8 <= a.K && (a.K & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.w) & 15u) == 0)
+        return *reinterpret_cast<const uint4*>(p);
+    uint16_t v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = k + q < a.K ? p[q] : (uint16_t)0;
+    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+}
+
+// The last layer of a wide model: logits = A * W3^T + b3 on bfloat16 activations (at most BN classes), then the
+// arg-max per row and the scatter of the label.  128 rows per block, four waves of 32 rows each.
+template <int BN>
+__global__ __launch_bounds__(256) void mlp_last_layer(LayerArgs a)
+{
+    constexpr int MI = 1, NI = BN / 32;   // a wave owns 32 rows x BN columns
+    constexpr int WM = BM / 4;
     constexpr int A_CHUNKS = BM * BK / 8 / 256; // 16-byte chunks per thread per step
     constexpr int B_CHUNKS = (BN * BK / 8 + 255) / 256;
     constexpr int SM_AB = (BM + BN) * LDT * 2;
-    constexpr int SM_EPI = FINAL ? BM * (BN + 1) * 4 : 0;
+    constexpr int SM_EPI = BM * (BN + 1) * 4;
     constexpr int SM_BYTES = SM_AB > SM_EPI ? SM_AB : SM_EPI;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SM_BYTES];
     __shared__ uint32_t s_flow[BM];
@@ -51,19 +63,11 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
     total = total < a.esc_cap ? total : a.esc_cap;
     const uint32_t row0 = a.row_begin + blockIdx.x * BM; // first escalated row of this block
     if (row0 >= total) return;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const uint32_t col0 = blockIdx.y * BN;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wm = tid >> 6;
 
-    if (AMODE != A_BF16 || FINAL) {
-        if (tid < BM) {
-            // FINAL: the index the label goes to; otherwise the input row (clamped into the input)
-            uint32_t f = 0u;
-            if (row0 + tid < total) f = (FINAL && a.scatter) ? a.scatter[row0 + tid] : a.esc_idx[row0 + tid];
-            s_flow[tid] = (FINAL || f < a.n_rows) ? f : a.n_rows - 1u;
-        }
-        __syncthreads();
-    }
+    if (tid < BM) // the index the row's label goes to
+        s_flow[tid] = row0 + tid < total ? (a.scatter ? a.scatter[row0 + tid] : a.esc_idx[row0 + tid]) : 0u;
+    __syncthreads();
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -78,14 +82,12 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
 #pragma unroll
         for (int u = 0; u < A_CHUNKS; ++u) {
             const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
-            const bool ok = row0 + r < total;
-            const uint32_t flow = (AMODE != A_BF16) ? s_flow[r] : 0u;
-            ra[u] = load_a_chunk<AMODE>(a, ok, blockIdx.x * BM + r, flow, k0 + kq * 8);
+            ra[u] = load_a_chunk<A_BF16>(a, row0 + r < total, blockIdx.x * BM + r, 0u, k0 + kq * 8);
         }
 #pragma unroll
         for (int u = 0; u < B_CHUNKS; ++u) {
             const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
-            rb[u] = (r < (uint32_t)BN) ? load_w_chunk(a, col0 + r, k0 + kq * 8) : make_uint4(0, 0, 0, 0);
+            rb[u] = (r < (uint32_t)BN) ? load_w_chunk(a, r, k0 + kq * 8) : make_uint4(0, 0, 0, 0);
         }
         __syncthreads(); // previous step's fragment reads are done
 #pragma unroll
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
                 fa[i] = as_bf16x8(*reinterpret_cast<const uint4*>(As + (wm * WM + i * 32 + (lane & 31)) * LDT + kofs));
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-                fb[j] = as_bf16x8(*reinterpret_cast<const uint4*>(Bs + (wn * WN + j * 32 + (lane & 31)) * LDT + kofs));
+                fb[j] = as_bf16x8(*reinterpret_cast<const uint4*>(Bs + (j * 32 + (lane & 31)) * LDT + kofs));
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -118,54 +120,34 @@ __global__ __launch_bounds__(256) void mlp_layer(LayerArgs a)
     }
 
     // accumulator element v of lane l in a 32x32 block: row 8*(v/4) + 4*(l/32) + v%4, column l%32
-    if (!FINAL) {
+    __syncthreads(); // operand tiles are dead; reuse the space for the logits tile
+    float* Ls = reinterpret_cast<float*>(smem);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const uint32_t col = col0 + wn * WN + j * 32 + (lane & 31);
-                const float b = col < a.N ? a.bias[col] : 0.f;
+        for (int j = 0; j < NI; ++j) {
+            const uint32_t cl = j * 32 + (lane & 31);
+            const float b = cl < a.N ? a.bias[cl] : 0.f;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const uint32_t r = wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    if (row0 + r < total && col < a.ldh) {
-                        float y = acc[i][j][v] + b;
-                        y = y > 0.f ? y : 0.f;
-                        // columns in [N, ldh) are padding: written as zeros
-                        a.h_out[(size_t)(blockIdx.x * BM + r) * a.ldh + col] = col < a.N ? f32_to_bf16_bits(y) : (uint16_t)0;
-                    }
-                }
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t r = wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                Ls[r * (BN + 1) + cl] = acc[i][j][v] + b;
             }
-    } else {
-        __syncthreads(); // operand tiles are dead; reuse the space for the logits tile
-        float* Ls = reinterpret_cast<float*>(smem);
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const uint32_t cl = wn * WN + j * 32 + (lane & 31);
-                const float b = col0 + cl < a.N ? a.bias[col0 + cl] : 0.f;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const uint32_t r = wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    Ls[r * (BN + 1) + cl] = acc[i][j][v] + b;
-                }
-            }
-        __syncthreads();
-        if (tid < BM && row0 + tid < total) {
-            const float* lr = Ls + tid * (BN + 1);
-            uint32_t best = 0;
-            float bv = lr[0];
-            for (uint32_t c = 0; c < a.N; ++c) {
-                const float v = lr[c];
-                if (a.logits) a.logits[(size_t)(row0 + tid) * a.N + c] = v;
-                if (v > bv) {
-                    bv = v;
-                    best = c;
-                }
-            }
-            if (s_flow[tid] < a.n_labels) a.labels[s_flow[tid]] = (uint16_t)best;
         }
+    __syncthreads();
+    if (tid < BM && row0 + tid < total) {
+        const float* lr = Ls + tid * (BN + 1);
+        uint32_t best = 0;
+        float bv = lr[0];
+        for (uint32_t c = 0; c < a.N; ++c) {
+            const float v = lr[c];
+            if (a.logits) a.logits[(size_t)(row0 + tid) * a.N + c] = v;
+            if (v > bv) {
+                bv = v;
+                best = c;
+            }
+        }
+        if (s_flow[tid] < a.n_labels) a.labels[s_flow[tid]] = (uint16_t)best;
     }
 }
 
@@ -319,9 +301,9 @@ void launch_final(sf_ctx* ctx, const LayerArgs& a, uint32_t rows_cap)
 {
     dim3 grid((rows_cap + BM - 1) / BM, 1);
     if (a.N <= 32)
-        mlp_layer<A_BF16, 32, true><<<grid, 256, 0, ctx->stream>>>(a);
+        mlp_last_layer<32><<<grid, 256, 0, ctx->stream>>>(a);
     else
-        mlp_layer<A_BF16, 64, true><<<grid, 256, 0, ctx->stream>>>(a);
+        mlp_last_layer<64><<<grid, 256, 0, ctx->stream>>>(a);
 }
 
 // labels = pred for every flow; the slow labels are scattered over it afterwards
@@ -357,7 +339,16 @@ int run_slow(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows, 
         return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: weights or biases missing");
     if ((mlp->mu == nullptr) != (mlp->inv_sigma == nullptr))
         return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: mu and inv_sigma come together");
-    if (n_flows == 0 || esc_cap == 0 || n_rows == 0) return SF_OK;
+    if (n_flows == 0) return SF_OK;
+    if (pred && pred != labels) {
+        // labels = the fast prediction for every flow, also when nothing escalates (Section 4.4: the fast
+        // label stands unless the slow model replaces it)
+        if (!labels) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: labels is NULL");
+        uint32_t blocks = (n_flows + 2047) / 2048;
+        copy_labels<<<blocks, 256, 0, ctx->stream>>>(pred, labels, n_flows);
+        SF_LAUNCH_CHECK(ctx, "copy_labels");
+    }
+    if (esc_cap == 0 || n_rows == 0) return SF_OK;
     if ((feat == nullptr) == (raw_src == nullptr))
         return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: give exactly one of feat and raw_src");
     if (feat && mlp->n_in > feat_ld) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: n_in %u > feat_ld %u", mlp->n_in, feat_ld);
@@ -372,11 +363,6 @@ int run_slow(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows, 
     }
     if (!esc_idx || !esc_count || !labels) return sf::fail(ctx, SF_EINVAL, "sf_slow_infer: esc_idx, esc_count or labels is NULL");
     if (!scatter && esc_cap > n_flows) esc_cap = n_flows;
-    if (pred && pred != labels) {
-        uint32_t blocks = (n_flows + 2047) / 2048;
-        copy_labels<<<blocks, 256, 0, ctx->stream>>>(pred, labels, n_flows);
-        SF_LAUNCH_CHECK(ctx, "copy_labels");
-    }
 
     sf::Carve ws(ctx);
     const bool bf = mlp->dtype == SF_BF16;
@@ -477,7 +463,7 @@ int run_slow(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32_t n_rows, 
             a.ldh = 0;
             a.logits = logits;
             launch_final(ctx, a, R);
-            SF_LAUNCH_CHECK(ctx, "mlp_layer 3");
+            SF_LAUNCH_CHECK(ctx, "mlp_last_layer");
         }
         return SF_OK;
     }

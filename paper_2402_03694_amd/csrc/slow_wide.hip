@@ -152,8 +152,10 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
     }
 
     // epilogue: relu, bfloat16, stage the tile, then whole rows to memory
+    // (a column block past the last real one holds a repeat of that block's results: stored as zeros)
 #pragma unroll
-    for (int j = 0; j < WNI; ++j)
+    for (int j = 0; j < WNI; ++j) {
+        const bool real = nb0 + j < nb_total;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const uint32_t cl = wave * 64u + j * 32u + 8u * g + 4u * (lane >> 5); // column inside the tile
@@ -162,11 +164,13 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
                 const uint32_t row = i * 32u + (lane & 31u);
                 const float y0 = fmaxf(acc[i][j][4 * g + 0], 0.f), y1 = fmaxf(acc[i][j][4 * g + 1], 0.f);
                 const float y2 = fmaxf(acc[i][j][4 * g + 2], 0.f), y3 = fmaxf(acc[i][j][4 * g + 3], 0.f);
-                *reinterpret_cast<uint2*>(otile + row * WLDO + cl) = make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3));
+                *reinterpret_cast<uint2*>(otile + row * WLDO + cl) =
+                    real ? make_uint2(pack_bf16(y0, y1), pack_bf16(y2, y3)) : make_uint2(0u, 0u);
             }
         }
+    }
     __syncthreads();
-    // 64 chunks of 8 columns per row; columns in [N, ldh) are padding and were computed as zeros
+    // 64 chunks of 8 columns per row; columns in [N, ldh) are padding and hold zeros
     for (uint32_t c = tid; c < WBM * (WBN / 8); c += WWAVES * 64u) {
         const uint32_t r = c / (WBN / 8), k = (c % (WBN / 8)) * 8u;
         if (row0 + r < total && col0 + k < a.ldh) {
@@ -185,8 +189,7 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
 template <int AMODE>
 int launch_wide(sf_ctx* ctx, const LayerArgs& a, const void* w_ordered, uint32_t rows_cap)
 {
-    SF_HIP(ctx, hipFuncSetAttribute((const void*)mlp_wide_layer<AMODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)kWideLds));
+    SF_ALLOW_LDS(ctx, sf::kLdsWide + AMODE, mlp_wide_layer<AMODE>);
     dim3 grid((rows_cap + WBM - 1) / WBM, (a.ldh + WBN - 1) / WBN);
     mlp_wide_layer<AMODE><<<grid, WWAVES * 64, kWideLds, ctx->stream>>>(a, (const uint4*)w_ordered);
     SF_LAUNCH_CHECK(ctx, "mlp_wide_layer");

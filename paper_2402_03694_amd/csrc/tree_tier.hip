@@ -203,7 +203,7 @@ extern "C" int sf_fastest_infer(sf_ctx* ctx, const float* feat, uint32_t feat_ld
     SF_LAUNCH_CHECK(ctx, "tree_prepare");
     const uint32_t lds_levels = tree->depth < kLdsLevels ? tree->depth : kLdsLevels;
     const size_t lds = (size_t)tree->n_features * 256 * sizeof(float) + (size_t)((1u << lds_levels) - 1u) * sizeof(uint2);
-    SF_HIP(ctx, hipFuncSetAttribute((const void*)tree_walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    SF_ALLOW_LDS(ctx, sf::kLdsTreeWalk, tree_walk);
     uint32_t grid = (n_flows + 255) / 256;
     uint32_t per_cu = (uint32_t)((160u * 1024u) / (lds + 256));
     per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);

@@ -262,6 +262,59 @@ def test_slow_infer_row_chunks_and_cap():
         assert np.array_equal(labels2[beyond], g_pred[beyond])
 
 
+@pytest.mark.parametrize("dims", [(64, 352, 480, 10), (64, 480, 352, 10), (64, 1056, 608, 10), (64, 608, 1056, 10)])
+def test_hidden_widths_of_32_modulo_64(dims):
+    """Hidden widths that end in half a 64-column wave tile (the first two run in the fused kernel, the others
+    layer by layer): the column block past the end must read as zeros in the next layer."""
+    cfg, pk, feat, forest, mlp = _small(2, 1500 + 9, mlp_dims=dims)
+    vmin = 15
+    want = oracle.classify(pk, cfg.depths, forest, vmin, mlp, n_threads=8)
+    run = _run(cfg, pk, forest, mlp)
+    run.featurize()
+    _, g_pred, _, _ = run.fast_infer()
+    esc, cnt = run.route(vmin)
+    assert cnt == want["esc_idx"].size and cnt > 300
+    logits, labels = run.slow_infer()
+    _check_slow(cfg, logits, labels, want["logits"], want["labels"], esc, g_pred, BF16_TOL, BF16_MARGIN)
+
+
+def test_labels_are_the_fast_prediction_when_nothing_escalates():
+    """Section 4.4's label rule with an empty list and with a capacity of zero: labels = pred for every flow."""
+    import torch
+    for cfg_id in (1, 2, 4):
+        cfg, pk, feat, forest, mlp = _small(cfg_id, 700 + 3)
+        run = _run(cfg, pk, forest, mlp)
+        run.featurize()
+        _, g_pred, _, _ = run.fast_infer()
+        esc, cnt = run.route(0)                     # no vote count is below zero
+        assert cnt == 0
+        _, labels = run.slow_infer()
+        assert np.array_equal(labels, g_pred)
+        run.labels.fill_(-1)
+        run.ctx.sf_slow_infer(run.mlp, run.esc_idx, run.esc_count, run.labels, feat=run.feat, esc_cap=0, pred=run.pred)
+        torch.cuda.synchronize()
+        assert np.array_equal(run.labels.cpu().numpy().view(np.uint16), g_pred)
+
+
+def test_featurize_packet_arrays_off_their_natural_alignment():
+    """Packet arrays that start 2, 4 and 1 bytes into an allocation (a caller's slice): same features."""
+    import torch
+    import paper_2402_03694_amd as sf
+    cfg = synth.get_config(2)
+    pk = synth.make_packets(cfg, n_flows=3000 + 7)
+    want, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=8)
+    dev = "cuda:0"
+    d = sf.packets_to_device(pk, dev)
+    shift = lambda t: torch.cat([t[:1], t])[1:]     # a view one element into a fresh allocation
+    off_by_one = sf.DevicePackets(d.flow_off, shift(d.pkt_size), shift(d.pkt_iat), shift(d.pkt_dir))
+    assert off_by_one.pkt_size.data_ptr() % 16 == 2 and off_by_one.pkt_iat.data_ptr() % 16 == 4
+    ctx = sf.ServeFlow(4096)
+    feat = torch.full((pk.n_flows, cfg.n_features), -1.0, dtype=torch.float32, device=dev)
+    ctx.sf_featurize(off_by_one, cfg.depths, feat)
+    torch.cuda.synchronize()
+    _assert_feat_equal(feat.cpu().numpy(), want, pk)
+
+
 def test_error_paths_return_codes():
     import torch
     import paper_2402_03694_amd as sf
