@@ -16,7 +16,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "serveflow_oracle.c")
-_LIB = os.path.join(_HERE, "libsf_oracle.so")
+# SF_ORACLE_SANITIZE=1: a second build with AddressSanitizer and UndefinedBehaviorSanitizer (the process must
+# have gcc's libasan preloaded); the arithmetic flags stay the same, so every pin must still hold
+_SANITIZE = os.environ.get("SF_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "libsf_oracle_san.so" if _SANITIZE else "libsf_oracle.so")
 
 CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
           "-fno-unsafe-math-optimizations", "-Wall", "-Wextra"]
@@ -26,7 +29,8 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (one second); returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", tmp, "-lm"])
+        extra = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] if _SANITIZE else []
+        subprocess.check_call(["gcc", *CFLAGS, *extra, _SRC, "-o", tmp, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 

@@ -12,7 +12,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libserveflow_hip.so")
+# SERVEFLOW_LIB names another build of the same library (the host-sanitized one of build.build_host_sanitized)
+LIB_PATH = os.environ.get("SERVEFLOW_LIB") or os.path.join(_HERE, "libserveflow_hip.so")
 
 SF_OK, SF_EINVAL, SF_ENOMEM, SF_EHIP, SF_EUNSUPPORTED, SF_EDATA = 0, -1, -2, -3, -4, -5
 SF_F32, SF_BF16 = 0, 1

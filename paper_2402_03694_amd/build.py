@@ -49,5 +49,34 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(ROOT, "_build", "libserveflow_hip_hostsan.so")
+CLANG_ASAN_RUNTIME = "/opt/rocm/llvm/lib/clang"
+
+
+def build_host_sanitized() -> str:
+    """A second copy of the library whose HOST code (argument checks, the threshold algorithms, workspace
+    arithmetic) is instrumented with AddressSanitizer and UndefinedBehaviorSanitizer; the device code is
+    built as always.  For CPU-side tests only: load it with the sanitizer runtime preloaded
+    (asan_runtime()) and SERVEFLOW_LIB pointing at it."""
+    os.makedirs(os.path.dirname(SAN_LIB), exist_ok=True)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + [
+        "-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+        "-Xarch_host", "-fno-sanitize-recover=undefined", "-shared-libsan"]
+    cmd = [hipcc, *flags, "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, *sources(), "-o", SAN_LIB]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc (host sanitizers) failed:\n" + res.stdout)
+    return SAN_LIB
+
+
+def asan_runtime() -> str:
+    """Path of the AddressSanitizer runtime that matches hipcc's host compiler."""
+    hits = glob.glob(os.path.join(CLANG_ASAN_RUNTIME, "*", "lib", "linux", "libclang_rt.asan-x86_64.so"))
+    if not hits:
+        raise RuntimeError("no libclang_rt.asan-x86_64.so under " + CLANG_ASAN_RUNTIME)
+    return sorted(hits)[-1]
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
