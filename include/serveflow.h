@@ -305,8 +305,9 @@ int sf_route_score(sf_ctx* ctx, const float* score, uint32_t n_flows, float thre
 
 /* Algorithm 1 (universal uncertainty thresholds) on a real-valued score: for each quantile q the
  * element at 1-based position ceil(q * n_flows) of the ascending order of score (device array),
- * found exactly by two 16-bit histogram passes over order-preserving keys, no sort.  host_q and
- * host_thresholds are HOST arrays of n_q entries.  Escalating the flows with score above the
+ * found exactly by radix selection on the device (three histogram passes over order-preserving keys,
+ * no sort, no host round trip between the passes).  host_q and host_thresholds are HOST arrays of n_q
+ * entries (at most 256).  Escalating the flows with score above the
  * threshold assigns at most a fraction 1 - q of them.  Waits for the stream. */
 int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_flows, const double* host_q, uint32_t n_q,
                        float* host_thresholds);
@@ -329,7 +330,8 @@ int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_flows, const 
  *
  * table: caller-owned device memory of sf_join_table_bytes(cap_log2) bytes, 16-byte aligned,
  * zero-filled before its first use, holding 2^cap_log2 slots per side (keep each side at most
- * half full).  The workspace of the context must have sf_join_workspace_bytes(cap_log2) bytes.
+ * half full) and, behind them, one occupancy word per 1,024 slots (a step does not sweep stretches
+ * of the tables in which nothing has been stored since they were last swept).  The workspace of the context must have sf_join_workspace_bytes(cap_log2) bytes.
  * pair_q3 / pair_q2: [pair_cap], pair k = (pair_q3[k], pair_q2[k]) in no particular order;
  * *n_pairs (device) = number of pairs found (pairs beyond pair_cap are lost and counted).
  * stats: optional device array of 4 words: discarded after the timeout, arrivals that found

@@ -80,7 +80,7 @@ enum LdsSlot { kLdsForest = 0 /* 12 variants */, kLdsTreeWalk = 12, kLdsWide = 1
 size_t forest_pack_bytes(uint32_t n_trees, uint32_t depth);
 size_t route_scratch_bytes(uint32_t n_flows);
 size_t tree_tier_bytes(uint32_t depth);
-constexpr size_t kQuantileBins = 65536; // bins of one radix pass of sf_score_quantiles
+constexpr size_t kQuantileScratch = 32768; // histograms, selection state and results of sf_score_quantiles
 size_t slow_row_bytes(uint32_t n_h1, uint32_t n_h2, int dtype);
 constexpr uint32_t kSlowMinRows = 256;     // smallest row chunk sf_slow_infer can work with
 constexpr uint32_t kSlowWantRows = 1 << 18; // chunk sf_workspace_bytes provisions for

@@ -56,7 +56,7 @@ extern "C" size_t sf_workspace_bytes(uint32_t max_flows, uint32_t n_trees, uint3
     total = align_up(total) + forest_pack_bytes(n_trees, tree_depth);
     total = align_up(total) + route_scratch_bytes(max_flows);
     total = align_up(total) + tree_tier_bytes(SF_MAX_TREE_DEPTH); // the single-tree tier at any depth
-    total = align_up(total) + kQuantileBins * 4;                  // histogram of sf_score_quantiles
+    total = align_up(total) + kQuantileScratch;                   // histograms and state of sf_score_quantiles
     if (n_h1 || n_h2) {
         // operand-ordered copies of the three weight matrices
         total = align_up(total) + reordered_bytes(n_h1, n_in ? n_in : 1) + reordered_bytes(n_h2, n_h1 ? n_h1 : 1) +

@@ -66,6 +66,7 @@ __device__ __forceinline__ void wave_count(uint32_t* counter, bool want)
 
 struct JoinArgs {
     Slot* table[2]; // [0] queue 3, [1] queue 2
+    uint32_t* used[2]; // per side, one word per kChunk slots: non-zero once a record was stored there since the last sweep
     uint32_t mask;  // slots per table - 1
     uint32_t now, timeout;
     Slot* list;     // scratch: survivors, side s in list[s * slots ...]
@@ -100,6 +101,10 @@ __global__ __launch_bounds__(256) void join_collect(JoinArgs a)
     for (uint32_t c = wave; c < 2u * chunks_per_side; c += n_waves) {
         const uint32_t side = c >= chunks_per_side ? 1u : 0u;
         const uint32_t first = (c - side * chunks_per_side) * kChunk;
+        // nothing was stored in this stretch since it was last swept: every slot is still empty
+        uint32_t* used = a.used[side] + (c - side * chunks_per_side);
+        if (*used == 0u) continue; // the same word in every lane: the wave skips together
+        if (lane == 0) *used = 0u; // the sweep below empties the stretch (the re-insert marks what it refills)
         Slot* t = a.table[side];
         // pass 1: who survives (one 64-bit lane mask per trip, the same in every lane)
         unsigned long long keep[kChunkTrips];
@@ -140,9 +145,10 @@ __global__ __launch_bounds__(256) void join_collect(JoinArgs a)
     }
 }
 
-// claim a free slot of `table` for id (probing from its home slot) and fill it; false if the table is full
-__device__ __forceinline__ bool insert_slot(Slot* table, uint32_t mask, unsigned long long id, uint32_t val, uint32_t stamp,
-                                            bool* duplicate)
+// claim a free slot of `table` for id (probing from its home slot) and fill it; false if the table is full.
+// used: the side's occupancy words; the stretch of the claimed slot is marked (every writer stores the same 1).
+__device__ __forceinline__ bool insert_slot(Slot* table, uint32_t* used, uint32_t mask, unsigned long long id, uint32_t val,
+                                            uint32_t stamp, bool* duplicate)
 {
     uint32_t p = slot_of(id, mask);
     for (uint32_t tries = 0; tries <= mask; ++tries, p = (p + 1u) & mask) {
@@ -152,6 +158,7 @@ __device__ __forceinline__ bool insert_slot(Slot* table, uint32_t mask, unsigned
             if (seen == kEmpty) {
                 table[p].val = val;
                 table[p].stamp = stamp;
+                used[p / kChunk] = 1u;
                 return true;
             }
         }
@@ -171,7 +178,7 @@ __global__ __launch_bounds__(256) void join_reinsert(JoinArgs a)
         for (uint32_t g = blockIdx.x * blockDim.x + threadIdx.x; g < n; g += gridDim.x * blockDim.x) {
             const Slot v = a.list[(size_t)side * slots + g];
             bool dup = false;
-            insert_slot(a.table[side], a.mask, v.id, v.val, v.stamp, &dup); // cannot fail: it fitted before
+            insert_slot(a.table[side], a.used[side], a.mask, v.id, v.val, v.stamp, &dup); // cannot fail: it fitted before
         }
     }
 }
@@ -210,7 +217,7 @@ __device__ __forceinline__ void arrive_one(const JoinArgs& a, const unsigned lon
             }
         }
         bool dup = false, stored = true;
-        if (!matched) stored = insert_slot(own, a.mask, id, val, a.now, &dup);
+        if (!matched) stored = insert_slot(own, a.used[SIDE], a.mask, id, val, a.now, &dup);
         what = matched ? 1 : (!stored ? 2 : (dup ? 3 : 0));
         pair_val = pv;
     }
@@ -281,10 +288,13 @@ size_t join_scratch_bytes(uint32_t cap_log2)
 }
 } // namespace sf
 
+// occupancy words per side (one per kChunk slots), padded to whole 16-byte units
+static size_t used_words(uint32_t cap_log2) { return ((((size_t)1 << cap_log2) + kChunk - 1) / kChunk + 3) / 4 * 4; }
+
 extern "C" size_t sf_join_table_bytes(uint32_t cap_log2)
 {
     if (cap_log2 < 4 || cap_log2 > 28) return 0;
-    return ((size_t)2 << cap_log2) * sizeof(Slot);
+    return ((size_t)2 << cap_log2) * sizeof(Slot) + 2 * used_words(cap_log2) * sizeof(uint32_t);
 }
 
 extern "C" size_t sf_join_workspace_bytes(uint32_t cap_log2)
@@ -317,6 +327,8 @@ extern "C" int sf_join_step(sf_ctx* ctx, const sf_join_table* table, uint32_t no
     JoinArgs a;
     a.table[0] = (Slot*)table->slots;
     a.table[1] = (Slot*)table->slots + slots;
+    a.used[0] = (uint32_t*)((Slot*)table->slots + 2 * (size_t)slots);
+    a.used[1] = a.used[0] + used_words(table->cap_log2);
     a.mask = slots - 1u;
     a.now = now;
     a.timeout = timeout;

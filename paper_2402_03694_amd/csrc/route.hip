@@ -229,7 +229,10 @@ __global__ __launch_bounds__(256) void hist_class_scores(const uint16_t* __restr
     }
 }
 
-// ---- calibration on a real-valued score: exact order statistics by two 16-bit histograms ------
+// ---- calibration on a real-valued score: exact order statistics by radix selection on the device ------
+// Three histogram passes over order-preserving 32-bit keys (11 + 11 + 10 bits); after each pass one small
+// block finds the bin that holds the wanted rank and narrows the key prefix.  Everything stays on the
+// device until the thresholds are read back.
 
 // order-preserving 32-bit key of a binary32 value (negative values below positive ones)
 __device__ __forceinline__ uint32_t float_key(float x)
@@ -238,17 +241,90 @@ __device__ __forceinline__ uint32_t float_key(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// hist[key >> 16] += 1 for every score (prefix_on = 0), or hist[key & 0xFFFF] += 1 for the scores
-// whose upper half equals prefix (prefix_on = 1)
-__global__ __launch_bounds__(256) void hist_float_keys(const float* __restrict__ score, uint32_t n, uint32_t prefix_on,
-                                                       uint32_t prefix, uint32_t* __restrict__ hist)
+constexpr uint32_t kSelBins = 2048;
+constexpr uint32_t kMaxQuantiles = 256;
+
+struct SelState {
+    uint32_t prefix; // the key bits fixed so far (right-aligned)
+    uint32_t rank;   // 1-based position of the wanted element among the scores that share the prefix
+};
+
+// hist[(key >> shift) & mask] += 1 for every score whose key has the state's prefix above prefix_shift
+// (st == NULL: every score).  A block counts in shared memory; lanes of a wave with the same bin are
+// counted with one add (scores cluster: most of a wave lands in a handful of bins).
+__global__ __launch_bounds__(256) void sel_hist(const float* __restrict__ score, uint32_t n, uint32_t shift, uint32_t mask,
+                                                uint32_t prefix_shift, const SelState* __restrict__ st,
+                                                uint32_t* __restrict__ hist)
 {
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
-        const uint32_t k = float_key(score[i]);
-        if (!prefix_on)
-            atomicAdd(&hist[k >> 16], 1u);
-        else if ((k >> 16) == prefix)
-            atomicAdd(&hist[k & 0xFFFFu], 1u);
+    __shared__ uint32_t sh[kSelBins];
+    for (uint32_t b = threadIdx.x; b < kSelBins; b += blockDim.x) sh[b] = 0;
+    __syncthreads();
+    const bool all = st == nullptr;
+    const uint32_t prefix = all ? 0u : st->prefix;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t rounded = (n + 63u) & ~63u; // whole waves stay in the loop together
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < rounded; i += (uint64_t)gridDim.x * blockDim.x) {
+        bool in = i < n;
+        const uint32_t key = in ? float_key(score[i]) : 0u;
+        in = in && (all || (key >> prefix_shift) == prefix);
+        const uint32_t bin = (key >> shift) & mask;
+        unsigned long long todo = __ballot(in);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const uint32_t lb = (uint32_t)__shfl((int)bin, leader, 64);
+            const unsigned long long same = __ballot(in && bin == lb);
+            if ((int)lane == leader) atomicAdd(&sh[lb], (uint32_t)__popcll(same));
+            todo &= ~same;
+        }
+    }
+    __syncthreads();
+    for (uint32_t b = threadIdx.x; b < kSelBins; b += blockDim.x)
+        if (sh[b]) atomicAdd(&hist[b], sh[b]);
+}
+
+// One block.  Finds the bin of hist[0..bins) that holds the state's rank, appends its `bits` bits to the
+// prefix and reduces the rank to the position inside that bin.  first_rank != 0 starts a new selection
+// (prefix empty, rank = first_rank).  clear (may be hist itself) is zero-filled for the next pass.
+// out != NULL (last pass): the finished key is turned back into the binary32 value it encodes.
+__global__ __launch_bounds__(256) void sel_pick(const uint32_t* __restrict__ hist, uint32_t bins, uint32_t bits,
+                                                SelState* __restrict__ st, uint32_t first_rank, uint32_t* clear,
+                                                float* __restrict__ out)
+{
+    __shared__ uint32_t sh[kSelBins];
+    __shared__ uint32_t part[256];
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t b = tid; b < kSelBins; b += 256u) sh[b] = b < bins ? hist[b] : 0u;
+    __syncthreads();
+    for (uint32_t b = tid; b < kSelBins; b += 256u) clear[b] = 0u;
+    constexpr uint32_t per = kSelBins / 256u;
+    uint32_t mine = 0;
+    for (uint32_t k = 0; k < per; ++k) mine += sh[tid * per + k];
+    part[tid] = mine;
+    __syncthreads();
+    for (uint32_t d = 1; d < 256u; d <<= 1) { // inclusive prefix sums over the threads' totals
+        const uint32_t v = tid >= d ? part[tid - d] : 0u;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    const uint32_t rank = first_rank ? first_rank : st->rank;
+    const uint32_t prefix = first_rank ? 0u : st->prefix;
+    const uint32_t total = part[255];
+    const uint32_t want = rank < 1u ? 1u : (rank > total ? total : rank); // total >= rank by construction
+    const uint32_t incl = part[tid], excl = incl - mine;
+    if (want > excl && want <= incl) { // exactly one thread
+        uint32_t seen = excl, bin = tid * per;
+        for (uint32_t k = 0; k < per; ++k) {
+            if (seen + sh[tid * per + k] >= want) {
+                bin = tid * per + k;
+                break;
+            }
+            seen += sh[tid * per + k];
+        }
+        const uint32_t key = (prefix << bits) | bin;
+        st->prefix = key;
+        st->rank = want - seen;
+        if (out) *out = __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
     }
 }
 
@@ -525,56 +601,37 @@ extern "C" int sf_score_quantiles(sf_ctx* ctx, const float* score, uint32_t n_fl
     if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_score_quantiles: ctx is NULL");
     if (!score || !host_q || !host_thresholds || n_flows == 0)
         return sf::fail(ctx, SF_EINVAL, "sf_score_quantiles: score, host_q or host_thresholds missing, or no flows");
+    if (n_q == 0) return SF_OK;
+    if (n_q > kMaxQuantiles) return sf::fail(ctx, SF_EUNSUPPORTED, "sf_score_quantiles: %u quantiles, at most %u per call", n_q, kMaxQuantiles);
     sf::Carve ws(ctx);
-    uint32_t* d_hist = (uint32_t*)ws.take(sf::kQuantileBins * 4);
-    if (!d_hist) return sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: workspace too small for %zu bytes", sf::kQuantileBins * 4);
-    uint32_t* h = new (std::nothrow) uint32_t[sf::kQuantileBins];
-    if (!h) return sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: out of host memory");
+    uint32_t* hist_all = (uint32_t*)ws.take(kSelBins * 4);  // pass 1, shared by every quantile
+    uint32_t* hist = (uint32_t*)ws.take(kSelBins * 4);      // passes 2 and 3 of the quantile at hand
+    SelState* st = (SelState*)ws.take(sizeof(SelState));
+    float* d_out = (float*)ws.take((size_t)n_q * 4);
+    if (!hist_all || !hist || !st || !d_out)
+        return sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: workspace too small for %zu bytes", sf::kQuantileScratch);
     uint32_t blocks = (n_flows + 256 * 16 - 1) / (256 * 16);
     blocks = blocks > 2048 ? 2048 : blocks;
-    // one pass over the upper 16 key bits, then one pass per quantile over the lower 16 bits of
-    // the scores that share the upper half of the wanted element
-    auto histogram = [&](uint32_t prefix_on, uint32_t prefix) -> int {
-        hist_zero<<<sf::kQuantileBins / 256, 256, 0, ctx->stream>>>(d_hist, sf::kQuantileBins);
-        SF_LAUNCH_CHECK(ctx, "hist_zero");
-        hist_float_keys<<<blocks, 256, 0, ctx->stream>>>(score, n_flows, prefix_on, prefix, d_hist);
-        SF_LAUNCH_CHECK(ctx, "hist_float_keys");
-        SF_HIP(ctx, hipMemcpyAsync(h, d_hist, sf::kQuantileBins * 4, hipMemcpyDeviceToHost, ctx->stream));
-        SF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        return SF_OK;
-    };
-    int rc = histogram(0, 0);
-    uint32_t* hi = nullptr;
-    if (rc == SF_OK) {
-        hi = new (std::nothrow) uint32_t[sf::kQuantileBins];
-        if (!hi) rc = sf::fail(ctx, SF_ENOMEM, "sf_score_quantiles: out of host memory");
+    hist_zero<<<(2 * kSelBins + 255) / 256, 256, 0, ctx->stream>>>(hist_all, kSelBins);
+    hist_zero<<<(2 * kSelBins + 255) / 256, 256, 0, ctx->stream>>>(hist, kSelBins);
+    SF_LAUNCH_CHECK(ctx, "hist_zero");
+    sel_hist<<<blocks, 256, 0, ctx->stream>>>(score, n_flows, 21u, 0x7FFu, 0u, nullptr, hist_all);
+    SF_LAUNCH_CHECK(ctx, "sel_hist");
+    for (uint32_t j = 0; j < n_q; ++j) {
+        // 1-based position ceil(q * n) in the ascending order (Algorithm 1), clamped to 1..n
+        double pos = std::ceil(host_q[j] * (double)n_flows);
+        if (!(pos >= 1.0)) pos = 1.0;
+        if (pos > (double)n_flows) pos = (double)n_flows;
+        sel_pick<<<1, 256, 0, ctx->stream>>>(hist_all, kSelBins, 11u, st, (uint32_t)pos, hist, nullptr);
+        sel_hist<<<blocks, 256, 0, ctx->stream>>>(score, n_flows, 10u, 0x7FFu, 21u, st, hist);
+        sel_pick<<<1, 256, 0, ctx->stream>>>(hist, kSelBins, 11u, st, 0u, hist, nullptr);
+        sel_hist<<<blocks, 256, 0, ctx->stream>>>(score, n_flows, 0u, 0x3FFu, 10u, st, hist);
+        sel_pick<<<1, 256, 0, ctx->stream>>>(hist, 1024u, 10u, st, 0u, hist, d_out + j);
+        SF_LAUNCH_CHECK(ctx, "sel_pick");
     }
-    if (rc == SF_OK) {
-        for (size_t b = 0; b < sf::kQuantileBins; ++b) hi[b] = h[b];
-        for (uint32_t j = 0; j < n_q && rc == SF_OK; ++j) {
-            // 1-based position ceil(q * n) in the ascending order (Algorithm 1), clamped to 1..n
-            double pos = std::ceil(host_q[j] * (double)n_flows);
-            if (!(pos >= 1.0)) pos = 1.0;
-            if (pos > (double)n_flows) pos = (double)n_flows;
-            uint64_t want = (uint64_t)pos, seen = 0;
-            uint32_t top = 0;
-            for (; top < sf::kQuantileBins - 1 && seen + hi[top] < want; ++top) seen += hi[top];
-            rc = histogram(1, top);
-            if (rc != SF_OK) break;
-            want -= seen;
-            seen = 0;
-            uint32_t low = 0;
-            for (; low < sf::kQuantileBins - 1 && seen + h[low] < want; ++low) seen += h[low];
-            const uint32_t key = (top << 16) | low;
-            const uint32_t bits = (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
-            float f;
-            memcpy(&f, &bits, 4);
-            host_thresholds[j] = f;
-        }
-    }
-    delete[] h;
-    delete[] hi;
-    return rc;
+    SF_HIP(ctx, hipMemcpyAsync(host_thresholds, d_out, (size_t)n_q * 4, hipMemcpyDeviceToHost, ctx->stream));
+    SF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return SF_OK;
 }
 
 extern "C" int sf_class_score_histogram(sf_ctx* ctx, const uint16_t* top_votes, const uint16_t* pred, const uint16_t* truth,
