@@ -1,15 +1,13 @@
 // Step 1: per-flow statistics of the first k packets (context length k, Section 3.1 of the
 // paper) and the unpacking of raw header bits (Section 4.1).
 //
-// One lane owns one flow and keeps its packets in registers.  Every binary32 operation is
-// issued on its own, in packet order (the file is compiled without floating-point
-// contraction), so the result does not depend on how flows are spread over lanes; a packet
-// outside a group contributes +0.0 to that group's running sums, which leaves them unchanged.
-// Order statistics (median, min, max) come from a compare-exchange sorting network over
-// order-preserving integer keys, padded with the largest key; the element at a data-dependent
-// rank is then read through a per-lane column of shared memory.  A block is one wave: its 64
-// feature rows are staged in shared memory per window and written out as full 128-byte runs.
+// One lane owns one flow and keeps its packets in registers; the statistics of a window are
+// computed by the shared device code in featurize_core.h (ordered sums, one sorting network and
+// one merge stage per quantity for the order statistics), so the result does not depend on how
+// flows are spread over lanes.  A block is one wave: its 64 feature rows are staged in shared
+// memory per window and written out as full 128-byte runs.
 #include "common.h"
+#include "featurize_core.h"
 
 namespace {
 
@@ -28,142 +26,8 @@ struct FeatArgs {
     float* feat;
     uint32_t ld;
     uint32_t wide_ok; // the packet arrays start on 16-byte (size, time) and 8-byte (direction) boundaries
+    uint32_t store16; // feat is 16-byte aligned and ld a multiple of 4: rows can be written in 16-byte pieces
 };
-
-// float -> unsigned key with the same order (negative values: all bits flipped, others: sign set)
-__device__ __forceinline__ uint32_t order_key(float x)
-{
-    const uint32_t b = __float_as_uint(x);
-    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
-}
-__device__ __forceinline__ float from_key(uint32_t u)
-{
-    return __uint_as_float(u ^ ((u & 0x80000000u) ? 0x80000000u : 0xFFFFFFFFu));
-}
-
-// Batcher's odd-even merge sort as a fixed network; every index is a compile-time constant
-// after unrolling, so the keys stay in registers.
-template <int N>
-__device__ __forceinline__ void sort_network(uint32_t (&a)[N])
-{
-#pragma unroll
-    for (int p = 1; p < N; p <<= 1) {
-#pragma unroll
-        for (int k = p; k >= 1; k >>= 1) {
-#pragma unroll
-            for (int j = k % p; j + k < N; j += 2 * k) {
-#pragma unroll
-                for (int i = 0; i < k; ++i) {
-                    if (i + j + k < N && (i + j) / (2 * p) == (i + j + k) / (2 * p)) {
-                        const uint32_t lo = a[i + j] < a[i + j + k] ? a[i + j] : a[i + j + k];
-                        const uint32_t hi = a[i + j] < a[i + j + k] ? a[i + j + k] : a[i + j];
-                        a[i + j] = lo;
-                        a[i + j + k] = hi;
-                    }
-                }
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ bool bit_of(uint64_t m, int j) { return (m >> j) & 1ull; }
-
-// Order statistics of one (quantity, group): keys of the group's members, the rest padded.
-template <int N, bool IS_TIME, int KMAX>
-__device__ __forceinline__ void order_stats(const float (&x)[KMAX], uint64_t gm, int cg, uint32_t* col,
-                                            float& mn, float& mx, float& med)
-{
-    uint32_t key[N];
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        // packet sizes are >= 0, so their bit pattern already orders like the value
-        const uint32_t k = IS_TIME ? order_key(x[i]) : __float_as_uint(x[i]);
-        key[i] = bit_of(gm, i) ? k : 0xFFFFFFFFu;
-    }
-    sort_network<N>(key);
-#pragma unroll
-    for (int i = 0; i < N; ++i) col[i * kWave] = key[i];
-    const int last = cg > 0 ? cg - 1 : 0;
-    const uint32_t klo = col[(last >> 1) * kWave], khi = col[(cg >> 1) * kWave], kmx = col[last * kWave];
-    mn = IS_TIME ? from_key(key[0]) : __uint_as_float(key[0]);
-    mx = IS_TIME ? from_key(kmx) : __uint_as_float(kmx);
-    const float lo = IS_TIME ? from_key(klo) : __uint_as_float(klo), hi = IS_TIME ? from_key(khi) : __uint_as_float(khi);
-    const float two = lo + hi;
-    med = (cg & 1) ? hi : two * 0.5f;
-}
-
-// The 32 statistics of one prefix window of m <= N packets, written to the lane's staged row.
-template <int N, int KMAX>
-__device__ __forceinline__ void window_stats(const float (&s)[KMAX], const float (&t)[KMAX], uint64_t dmask, int m,
-                                             uint32_t* col, float* row)
-{
-    static_assert(N <= KMAX, "window network larger than the register file of the flow");
-    const uint64_t valid = m >= 64 ? ~0ull : ((1ull << m) - 1ull);
-    const uint64_t m1 = dmask & valid, m0 = ~dmask & valid;
-    const int c1 = __popcll(m1), c0 = m - c1;
-    // pass 1: ordered sums
-    float sS0 = 0.f, sS1 = 0.f, sSa = 0.f, sT0 = 0.f, sT1 = 0.f, sTa = 0.f;
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const bool v = bit_of(valid, j), d0 = bit_of(m0, j), d1 = bit_of(m1, j);
-        const float a = s[j], b = t[j];
-        sSa = sSa + (v ? a : 0.f);
-        sS0 = sS0 + (d0 ? a : 0.f);
-        sS1 = sS1 + (d1 ? a : 0.f);
-        sTa = sTa + (v ? b : 0.f);
-        sT0 = sT0 + (d0 ? b : 0.f);
-        sT1 = sT1 + (d1 ? b : 0.f);
-    }
-    const float n0 = (float)(c0 > 0 ? c0 : 1), n1 = (float)(c1 > 0 ? c1 : 1), na = (float)(m > 0 ? m : 1);
-    const float mS0 = sS0 / n0, mS1 = sS1 / n1, mSa = sSa / na;
-    const float mT0 = sT0 / n0, mT1 = sT1 / n1, mTa = sTa / na;
-    // pass 2: ordered sums of squared deviations
-    float qS0 = 0.f, qS1 = 0.f, qSa = 0.f, qT0 = 0.f, qT1 = 0.f, qTa = 0.f;
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const bool v = bit_of(valid, j), d0 = bit_of(m0, j), d1 = bit_of(m1, j);
-        const float a = s[j], b = t[j];
-        const float ea = a - mSa, eb = b - mTa;
-        const float ea2 = ea * ea, eb2 = eb * eb;
-        qSa = qSa + (v ? ea2 : 0.f);
-        qTa = qTa + (v ? eb2 : 0.f);
-        const float ga = a - (d1 ? mS1 : mS0), gb = b - (d1 ? mT1 : mT0);
-        const float ga2 = ga * ga, gb2 = gb * gb;
-        qS0 = qS0 + (d0 ? ga2 : 0.f);
-        qS1 = qS1 + (d1 ? ga2 : 0.f);
-        qT0 = qT0 + (d0 ? gb2 : 0.f);
-        qT1 = qT1 + (d1 ? gb2 : 0.f);
-    }
-    // per group: assemble the ten statistics (for the larger networks the group index is a run-time
-    // loop so that the sorting network is emitted twice, not six times)
-    constexpr int kGroupUnroll = N <= 16 ? 3 : 1;
-#pragma unroll kGroupUnroll
-    for (int g = 0; g < 3; ++g) {
-        const uint64_t gm = g == 0 ? m0 : (g == 1 ? m1 : valid);
-        const int cg = g == 0 ? c0 : (g == 1 ? c1 : m);
-        const float ng = g == 0 ? n0 : (g == 1 ? n1 : na);
-        const float meanS = g == 0 ? mS0 : (g == 1 ? mS1 : mSa), meanT = g == 0 ? mT0 : (g == 1 ? mT1 : mTa);
-        const float ssS = g == 0 ? qS0 : (g == 1 ? qS1 : qSa), ssT = g == 0 ? qT0 : (g == 1 ? qT1 : qTa);
-        const float varS = ssS / ng, varT = ssT / ng;
-        float mnS, mxS, medS, mnT, mxT, medT;
-        order_stats<N, false, KMAX>(s, gm, cg, col, mnS, mxS, medS);
-        order_stats<N, true, KMAX>(t, gm, cg, col, mnT, mxT, medT);
-        const bool empty = cg == 0;
-        float* o = row + 10 * g;
-        o[0] = empty ? 0.f : meanS;
-        o[1] = empty ? 0.f : sqrtf(varS);
-        o[2] = empty ? 0.f : mnS;
-        o[3] = empty ? 0.f : mxS;
-        o[4] = empty ? 0.f : medS;
-        o[5] = empty ? 0.f : meanT;
-        o[6] = empty ? 0.f : sqrtf(varT);
-        o[7] = empty ? 0.f : mnT;
-        o[8] = empty ? 0.f : mxT;
-        o[9] = empty ? 0.f : medT;
-    }
-    row[30] = sSa; // total bytes: every partial sum is an integer below 2^24, so this is exact
-    row[31] = (float)m;
-}
 
 __device__ __forceinline__ void flow_range(const FeatArgs& a, uint32_t i, uint32_t& o, uint32_t& n)
 {
@@ -175,8 +39,50 @@ __device__ __forceinline__ void flow_range(const FeatArgs& a, uint32_t i, uint32
     n = e - b;
 }
 
+// A flow's packet records as loaded by the wide path (whole deepest window present, 16-byte aligned)
 template <int KMAX>
-__global__ __launch_bounds__(kWave) void featurize_wave(FeatArgs a)
+struct RawPackets {
+    uint4 sz[KMAX / 8];
+    float4 tm[KMAX / 4];
+    uint2 dr[KMAX / 8];
+};
+
+template <int KMAX>
+__device__ __forceinline__ void load_wide(const FeatArgs& a, uint32_t o, RawPackets<KMAX>& r)
+{
+#pragma unroll
+    for (int c = 0; c < KMAX / 8; ++c) {
+        r.sz[c] = *reinterpret_cast<const uint4*>(a.size + o + 8 * c);
+        r.tm[2 * c] = *reinterpret_cast<const float4*>(a.iat + o + 8 * c);
+        r.tm[2 * c + 1] = *reinterpret_cast<const float4*>(a.iat + o + 8 * c + 4);
+        r.dr[c] = *reinterpret_cast<const uint2*>(a.dir + o + 8 * c);
+    }
+}
+
+template <int KMAX>
+__device__ __forceinline__ void decode_wide(const RawPackets<KMAX>& r, float (&s)[KMAX], float (&t)[KMAX], uint64_t& dmask)
+{
+    dmask = 0;
+#pragma unroll
+    for (int c = 0; c < KMAX / 8; ++c) {
+        const uint32_t w[4] = {r.sz[c].x, r.sz[c].y, r.sz[c].z, r.sz[c].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            s[8 * c + 2 * k] = (float)(w[k] & 0xFFFFu);
+            s[8 * c + 2 * k + 1] = (float)(w[k] >> 16);
+        }
+        const float4 t0 = r.tm[2 * c], t1 = r.tm[2 * c + 1];
+        t[8 * c + 0] = t0.x; t[8 * c + 1] = t0.y; t[8 * c + 2] = t0.z; t[8 * c + 3] = t0.w;
+        t[8 * c + 4] = t1.x; t[8 * c + 5] = t1.y; t[8 * c + 6] = t1.z; t[8 * c + 7] = t1.w;
+        const uint32_t dw[2] = {r.dr[c].x, r.dr[c].y};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dmask |= (uint64_t)((dw[k >> 2] >> (8 * (k & 3))) & 1u) << (8 * c + k);
+    }
+}
+
+// (second launch bound: waves per SIMD the register allocation aims for: three up to 16 packets per flow)
+template <int KMAX>
+__global__ __launch_bounds__(kWave, (KMAX <= 16 ? 3 : 1)) void featurize_wave(FeatArgs a)
 {
     __shared__ uint32_t sort_col[KMAX * kWave]; // [rank][lane]
     __shared__ float tile[kWave * kRow];        // [lane][33]
@@ -192,25 +98,9 @@ __global__ __launch_bounds__(kWave) void featurize_wave(FeatArgs a)
     uint64_t dmask = 0;
     if (avail == KMAX && (o & 7u) == 0 && a.wide_ok) {
         // whole window present and 16-byte aligned (array bases included): wide loads
-#pragma unroll
-        for (int c = 0; c < KMAX / 8; ++c) {
-            const uint4 sz = *reinterpret_cast<const uint4*>(a.size + o + 8 * c);
-            const uint32_t w[4] = {sz.x, sz.y, sz.z, sz.w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                s[8 * c + 2 * k] = (float)(w[k] & 0xFFFFu);
-                s[8 * c + 2 * k + 1] = (float)(w[k] >> 16);
-            }
-            const float4 t0 = *reinterpret_cast<const float4*>(a.iat + o + 8 * c);
-            const float4 t1 = *reinterpret_cast<const float4*>(a.iat + o + 8 * c + 4);
-            t[8 * c + 0] = t0.x; t[8 * c + 1] = t0.y; t[8 * c + 2] = t0.z; t[8 * c + 3] = t0.w;
-            t[8 * c + 4] = t1.x; t[8 * c + 5] = t1.y; t[8 * c + 6] = t1.z; t[8 * c + 7] = t1.w;
-            const uint2 dd = *reinterpret_cast<const uint2*>(a.dir + o + 8 * c);
-            const uint32_t dw[2] = {dd.x, dd.y};
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                dmask |= (uint64_t)((dw[k >> 2] >> (8 * (k & 3))) & 1u) << (8 * c + k);
-        }
+        RawPackets<KMAX> raw;
+        load_wide<KMAX>(a, o, raw);
+        decode_wide<KMAX>(raw, s, t, dmask);
     } else {
 #pragma unroll
         for (int j = 0; j < KMAX; ++j) {
@@ -224,6 +114,11 @@ __global__ __launch_bounds__(kWave) void featurize_wave(FeatArgs a)
             }
         }
     }
+    // a time with its sign bit set anywhere in the wave: the order statistics take the general path
+    uint32_t sign_bits = 0;
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) sign_bits |= __float_as_uint(t[j]);
+    const bool signed_times = __any((int)(sign_bits >> 31));
     uint32_t* col = sort_col + lane;
     float* row = tile + lane * kRow;
     uint32_t rows = a.n_flows - tile0;
@@ -233,18 +128,29 @@ __global__ __launch_bounds__(kWave) void featurize_wave(FeatArgs a)
         const int m = avail < dw ? avail : dw;
         // the smallest network that covers every lane's window (wave-uniform choice)
         if (KMAX >= 64 && __any(m > 32))
-            window_stats<(KMAX >= 64 ? 64 : KMAX), KMAX>(s, t, dmask, m, col, row);
+            sffeat::window_stats<(KMAX >= 64 ? 64 : KMAX), KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
         else if (KMAX >= 32 && __any(m > 16))
-            window_stats<(KMAX >= 32 ? 32 : KMAX), KMAX>(s, t, dmask, m, col, row);
+            sffeat::window_stats<(KMAX >= 32 ? 32 : KMAX), KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
         else if (KMAX >= 16 && __any(m > 8))
-            window_stats<(KMAX >= 16 ? 16 : KMAX), KMAX>(s, t, dmask, m, col, row);
+            sffeat::window_stats<(KMAX >= 16 ? 16 : KMAX), KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
         else
-            window_stats<8, KMAX>(s, t, dmask, m, col, row);
+            sffeat::window_stats<8, KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
         __syncthreads();
-        // half a wave writes one staged row: 32 consecutive floats = one 128-byte run
-        const uint32_t c = lane & 31u, half = lane >> 5;
-        for (uint32_t r = half; r < rows; r += 2)
-            a.feat[(size_t)(tile0 + r) * a.ld + 32u * w + c] = tile[r * kRow + c];
+        if (a.store16) {
+            // eight lanes write one staged row (32 consecutive floats = one 128-byte run) as 16-byte pieces:
+            // a store instruction of the wave covers eight rows
+            const uint32_t c4 = (lane & 7u) * 4u;
+            for (uint32_t r = lane >> 3; r < rows; r += 8u) {
+                const float* src = tile + r * kRow + c4;
+                *reinterpret_cast<float4*>(a.feat + (size_t)(tile0 + r) * a.ld + 32u * w + c4) =
+                    make_float4(src[0], src[1], src[2], src[3]);
+            }
+        } else {
+            // half a wave writes one staged row, a float per lane
+            const uint32_t c = lane & 31u, half = lane >> 5;
+            for (uint32_t r = half; r < rows; r += 2)
+                a.feat[(size_t)(tile0 + r) * a.ld + 32u * w + c] = tile[r * kRow + c];
+        }
         __syncthreads();
     }
 }
@@ -319,6 +225,7 @@ extern "C" int sf_featurize(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg
     a.feat = feat;
     a.ld = feat_ld;
     a.wide_ok = (((uintptr_t)a.size | (uintptr_t)a.iat) & 15u) == 0 && ((uintptr_t)a.dir & 7u) == 0;
+    a.store16 = ((uintptr_t)feat & 15u) == 0 && (feat_ld & 3u) == 0;
     const uint32_t dmax = cfg->depth[cfg->n_windows - 1];
     const uint32_t grid = (a.n_flows + kWave - 1) / kWave;
     if (dmax <= 8)

@@ -89,6 +89,28 @@ def test_featurize_ties_and_duplicates():
     _assert_feat_equal(got, want, pk)
 
 
+@pytest.mark.parametrize("cfg_id,n", [(2, 2000 + 11), (4, 3000 + 7), (5, 1000 + 1)])
+def test_featurize_extreme_values_and_signed_times(cfg_id, n):
+    """Sizes 0 and 65535, times 0 and the largest finite value (they tie with or sit next to the padding of the
+    sorting network), one-direction flows, and, in every fourth wave, negative times (the general path of the
+    order statistics; no zeros there: the sign of a zero median is not defined by a sort)."""
+    cfg = synth.get_config(cfg_id)
+    pk = synth.make_packets(cfg, n_flows=n)
+    rng = np.random.default_rng(17)
+    pk.pkt_size = rng.choice(np.array([0, 0, 1, 40, 1500, 65535, 65535], np.uint16), size=pk.n_pkts)
+    iat = rng.choice(np.array([0.0, 0.0, 1e-38, 0.25, 3.0, 3.4028235e38], np.float32), size=pk.n_pkts)
+    lens = np.diff(pk.flow_off.astype(np.int64))
+    flow_of_pkt = np.repeat(np.arange(pk.n_flows), lens)
+    neg = (flow_of_pkt // 64) % 4 == 1
+    iat[neg] = rng.choice(np.array([-2.5, -1e-3, 0.5, 7.0, -3.0e38], np.float32), size=int(neg.sum()))
+    pk.pkt_iat = iat
+    one_dir = (flow_of_pkt // 64) % 4 == 2
+    pk.pkt_dir = np.where(one_dir, (flow_of_pkt % 2).astype(np.uint8), pk.pkt_dir)
+    want, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=8)
+    got, _ = _run(cfg, pk).featurize()
+    _assert_feat_equal(got, want, pk)
+
+
 def test_featurize_raw_bits():
     cfg = synth.get_config(3)
     pk = synth.make_packets(cfg, n_flows=300)
