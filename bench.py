@@ -389,17 +389,24 @@ class TwoTier:
             self.ctx.sf_fast_infer(self.feat, self.d_model, self.pred, self.top)
         torch.cuda.synchronize()
 
+    fused = False   # steps 1-3 through sf_featurize_fast_infer (one kernel) instead of two calls
+
     def step(self, vmin, ev=None, d_pk=None):
-        """The four calls over one device-resident batch; ev: five events recorded around them."""
+        """The calls of one pass over one device-resident batch; ev: five events recorded around them
+        (features | fast model | gate | slow model; in the fused form the first interval is empty)."""
         cfg, ctx = self.cfg, self.ctx
         d_pk = d_pk or self.d_pk
         n = d_pk.n_flows
         if ev:
             ev[0].record()
-        ctx.sf_featurize(d_pk, cfg.depths, self.feat)
+        if not self.fused:
+            ctx.sf_featurize(d_pk, cfg.depths, self.feat)
         if ev:
             ev[1].record()
-        if self.gbdt:
+        if self.fused:
+            ctx.sf_featurize_fast_infer(d_pk, cfg.depths, self.d_model, vmin, None if cfg.raw_pkts else self.feat, self.pred,
+                                        self.top)
+        elif self.gbdt:
             ctx.sf_gbdt_infer(self.feat, self.d_model, self.kind, self.pred, self.score, n_flows=n)
         else:
             ctx.sf_fast_infer(self.feat, self.d_model, self.pred, self.top, n_flows=n)
@@ -472,6 +479,31 @@ def kernel_report(tt, cfg_id, n, n_pkts, n_esc, avg, probe):
     """Per-call rooflines from the average call durations avg[4] (ms)."""
     cfg = tt.cfg
     k1b, k2b, k3b = algorithmic_bytes(cfg, n, n_pkts, n_esc / max(n, 1))
+    if tt.fused:
+        # one kernel for steps 1-3: packet records and offsets in, pred / top_votes out, and the feature rows of
+        # the escalated flows only (none when the slow model reads header bits)
+        fb = 7 * n_pkts + 4 * (n + 1) + 4 * n + (0 if cfg.raw_pkts else 4 * cfg.n_features * n_esc)
+        visits = float(n) * cfg.n_trees * cfg.tree_depth
+        a = fb / (avg[1] * 1e-3) / 1e9
+        fk = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
+              "traffic": measured_traffic("sf_featurize_fast_infer", cfg_id, n), "ms": float(avg[1]), "bytes": fb,
+              "node_visits": visits, "visits_per_s": visits / (avg[1] * 1e-3),
+              "note": "features, forest walk and score in one kernel: bound by gathers and vector arithmetic, not by HBM"}
+        if probe:
+            fk.update(gather_probe=probe, gather_bound_visits_per_s=probe["bound_visits_per_s"],
+                      gather_frac=fk["visits_per_s"] / probe["bound_visits_per_s"])
+        a3 = k3b / (avg[2] * 1e-3) / 1e9
+        tf = mlp_flops(cfg, n_esc) / (avg[3] * 1e-3) / 1e12
+        kernels = {"sf_featurize_fast_infer": fk,
+                   "sf_route": {"bound": "hbm", "achieved": a3, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a3 / HBM_PEAK_GBS,
+                                "traffic": measured_traffic("sf_route", cfg_id, n), "ms": float(avg[2]), "bytes": k3b},
+                   "sf_slow_infer": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic("sf_slow_infer", cfg_id, n),
+                                     "ms": float(avg[3]), "flops": mlp_flops(cfg, n_esc)}}
+        dominant = ["sf_featurize_fast_infer", "sf_featurize_fast_infer", "sf_route", "sf_slow_infer"][int(np.argmax(avg))]
+        roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+        roof["kernel"] = dominant
+        return roof, kernels
     flops = mlp_flops(cfg, n_esc)
     visits = float(n) * cfg.n_trees * cfg.tree_depth
 
@@ -636,6 +668,10 @@ def main():
                     help="how the gate's threshold is chosen where the workload names a target portion: one threshold "
                          "for all classes, or one per predicted class (Algorithm 2); auto = per-class for the headline "
                          "workload, universal elsewhere")
+    ap.add_argument("--calls", choices=["auto", "fused", "separate"], default="auto",
+                    help="steps 1-3 as one kernel (sf_featurize_fast_infer) or as sf_featurize + sf_fast_infer; auto = fused "
+                         "for the headline workload (whose shape the fused kernel covers), with the separate calls timed "
+                         "beside it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--join", action="store_true", help="time the queue join in front of the slow model instead")
     ap.add_argument("--copy-probe", action="store_true",
@@ -670,6 +706,17 @@ def main():
     n = args.flows or cfg.n_flows
     tt = TwoTier(cfg, n, dev)
     vmin, how, _ = tt.calibrate(args)
+    want_fused = args.calls == "fused" or (args.calls == "auto" and args.config == 2)
+    if want_fused:
+        # the fused kernel leaves the rows of the flows that stay with the fast model untouched: check that it ran
+        tt.fused = True
+        tt.feat.fill_(float("nan"))
+        tt.step(vmin)
+        torch.cuda.synchronize()
+        rows_written = int((~torch.isnan(tt.feat[:, 0])).sum().item())
+        n_esc0 = int(tt.esc_count.cpu().numpy().view(np.uint32)[0])
+        if cfg.raw_pkts == 0 and rows_written != n_esc0:
+            tt.fused = False        # this shape ran the separate kernels inside the library
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -680,6 +727,18 @@ def main():
     wall, call_ms = timed_steps(tt, vmin, args.steps, args.warmup)
     n_esc = int(tt.esc_count.cpu().numpy().view(np.uint32)[0])
     out = result_line(tt, args, args.config, vmin, how, n, tt.pk.n_pkts, n_esc, args.steps, wall, call_ms, probe)
+    out["config"]["calls"] = "sf_featurize_fast_infer + sf_route + sf_slow_infer" if tt.fused else \
+                             "sf_featurize + sf_fast_infer + sf_route + sf_slow_infer"
+    if tt.fused:
+        # the same step through the four separate calls
+        tt.fused = False
+        s_wall, s_ms = timed_steps(tt, vmin, args.steps, args.warmup)
+        _, s_kernels = kernel_report(tt, args.config, n, tt.pk.n_pkts, n_esc, s_ms.mean(axis=0), probe)
+        for v in s_kernels.values():
+            v.pop("gather_probe", None)
+        out["separate_calls"] = {"value": n * args.steps / s_wall, "unit": "flows/s", "ms_per_step": s_wall * 1e3 / args.steps,
+                                 "kernels": s_kernels}
+        tt.fused = True
     if args.gate == "per-class" and not tt.gbdt:
         # the same workload behind one threshold for all classes: the integer score then reaches only a few portions
         u_vmin, reached = tt.sf.sf_vmin_for_target(tt.hist, cfg.n_trees, args.target if args.target >= 0 else cfg.target_fracs[0])

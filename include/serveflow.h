@@ -406,6 +406,31 @@ int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32
                         const uint32_t* pair_row, const uint32_t* pair_flow, const uint32_t* n_pairs,
                         uint32_t pair_cap, uint32_t n_flows, const sf_mlp* mlp, float* logits, uint16_t* labels);
 
+/* ---- steps 1-3 in one kernel, all four steps in one call ----------------------------------------
+ * Sections 3.1 and 3.2: features from the first k packets, the fast model on every flow, the gate, the slow
+ * model on the flows the gate hands on.
+ *
+ * sf_featurize_fast_infer: the results of sf_featurize followed by sf_fast_infer (pred, top_votes), but for
+ * window depths up to 16 packets and forests that run one lane per flow both steps are ONE kernel that
+ * builds each tile of flows' features in shared memory and walks the forest there.  The feature matrix is
+ * then written only where the slow model will read it: row i of feat is written iff flow i escalates under
+ * the gate given by host_vmin / n_vmin (as sf_route: top_votes < vmin, or vmin[pred]); the other rows are
+ * left untouched.  feat = NULL: no row is written (a slow model that reads header bits needs none).
+ * Other shapes run the separate kernels and write every row (they need feat).
+ *
+ * sf_classify: all four steps: sf_featurize_fast_infer, sf_route, sf_slow_infer (with pred given and
+ * esc_cap = n_flows); the results are those of the four calls in turn with the same arguments, except for
+ * the rows of feat that are not written.  cfg->raw_pkts > 0: the slow model reads the header bits of pk
+ * (raw_pkts * raw_bits = mlp->n_in) and no feature row is kept.  logits: optional [n_flows][n_classes],
+ * row e belongs to flow esc_idx[e].  Both use workspace as the separate calls do. */
+int sf_featurize_fast_infer(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
+                            const uint16_t* host_vmin, uint32_t n_vmin, float* feat, uint32_t feat_ld,
+                            uint16_t* pred, uint16_t* top_votes);
+int sf_classify(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
+                const uint16_t* host_vmin, uint32_t n_vmin, const sf_mlp* mlp, float* feat, uint32_t feat_ld,
+                uint16_t* pred, uint16_t* top_votes, uint32_t* esc_idx, uint32_t* esc_count, float* logits,
+                uint16_t* labels);
+
 /* ---- measurement aid ---------------------------------------------------------------------------
  * Not a step of the method.  The walk of the fast model (Section 3.1: it sees every flow, so it sets the
  * service rate) is bound by gathers, not by memory bandwidth; sf_probe_gather measures what such gathers

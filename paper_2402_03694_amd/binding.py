@@ -26,7 +26,7 @@ EXPORTS = ("sf_workspace_bytes", "sf_create", "sf_destroy", "sf_last_error", "sf
            "sf_fast_infer_subset", "sf_route_subset", "sf_gbdt_infer", "sf_route_score", "sf_score_quantiles",
            "sf_class_score_histogram", "sf_per_class_thresholds", "sf_join_table_bytes", "sf_join_workspace_bytes",
            "sf_join_step", "sf_join_pending", "sf_slow_infer_pairs", "sf_forest_packed_bytes", "sf_forest_pack",
-           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order", "sf_route_static", "sf_probe_gather")
+           "sf_gbdt_pack", "sf_mlp_ordered_bytes", "sf_mlp_order", "sf_route_static", "sf_probe_gather", "sf_classify", "sf_featurize_fast_infer")
 
 
 class SfPackets(ctypes.Structure):
@@ -107,6 +107,12 @@ def load_library() -> ctypes.CDLL:
     lib.sf_route.argtypes = [vp, vp, vp, u32, ctypes.POINTER(ctypes.c_uint16), u32, vp, vp]
     lib.sf_route_static.restype = ctypes.c_int
     lib.sf_route_static.argtypes = lib.sf_route.argtypes
+    lib.sf_classify.restype = ctypes.c_int
+    lib.sf_classify.argtypes = [vp, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), ctypes.POINTER(SfForest),
+                                ctypes.POINTER(ctypes.c_uint16), u32, ctypes.POINTER(SfMlp), vp, u32, vp, vp, vp, vp, vp, vp]
+    lib.sf_featurize_fast_infer.restype = ctypes.c_int
+    lib.sf_featurize_fast_infer.argtypes = [vp, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), ctypes.POINTER(SfForest),
+                                            ctypes.POINTER(ctypes.c_uint16), u32, vp, u32, vp, vp]
     lib.sf_probe_gather.restype = ctypes.c_int
     lib.sf_probe_gather.argtypes = [vp, ctypes.c_int, u32, u32, u32, vp, vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.sf_vmin_from_theta.restype = u32
@@ -419,6 +425,28 @@ class ServeFlow:
         n = int(top_votes.shape[0]) if n_flows is None else n_flows
         self._check(self._lib.sf_route(self._h, _ptr(top_votes, torch.int16), _ptr(pred, torch.int16), n, arr, len(vm),
                                        _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
+
+    def sf_featurize_fast_infer(self, pk: DevicePackets, depths: Sequence[int], forest: DeviceForest, vmin,
+                                feat: Optional[torch.Tensor], pred: torch.Tensor, top_votes: torch.Tensor):
+        s, c, f = pk.c_struct(), _feat_cfg(depths), forest.c_struct()
+        vm = [int(vmin)] if isinstance(vmin, int) else [int(v) for v in vmin]
+        arr = (ctypes.c_uint16 * len(vm))(*vm)
+        self._check(self._lib.sf_featurize_fast_infer(
+            self._h, ctypes.byref(s), ctypes.byref(c), ctypes.byref(f), arr, len(vm), _ptr(feat, torch.float32),
+            int(feat.shape[1]) if feat is not None else 0, _ptr(pred, torch.int16), _ptr(top_votes, torch.int16)))
+
+    def sf_classify(self, pk: DevicePackets, depths: Sequence[int], forest: DeviceForest, vmin, mlp: DeviceMlp,
+                    feat: Optional[torch.Tensor], pred: torch.Tensor, top_votes: torch.Tensor, esc_idx: torch.Tensor,
+                    esc_count: torch.Tensor, labels: torch.Tensor, logits: Optional[torch.Tensor] = None,
+                    raw_pkts: int = 0, raw_bits: int = 0):
+        s, c, f, m = pk.c_struct(), _feat_cfg(depths, raw_pkts, raw_bits), forest.c_struct(), mlp.c_struct()
+        vm = [int(vmin)] if isinstance(vmin, int) else [int(v) for v in vmin]
+        arr = (ctypes.c_uint16 * len(vm))(*vm)
+        self._check(self._lib.sf_classify(
+            self._h, ctypes.byref(s), ctypes.byref(c), ctypes.byref(f), arr, len(vm), ctypes.byref(m),
+            _ptr(feat, torch.float32), int(feat.shape[1]) if feat is not None else 0, _ptr(pred, torch.int16),
+            _ptr(top_votes, torch.int16), _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32),
+            _ptr(logits, torch.float32), _ptr(labels, torch.int16)))
 
     def sf_route_static(self, top_votes: torch.Tensor, pred: Optional[torch.Tensor], vmin, esc_idx: torch.Tensor,
                         esc_count: torch.Tensor, n_flows: Optional[int] = None):

@@ -66,7 +66,7 @@ struct Carve {
 // whole of a compute unit's, once per context and kernel (the context remembers which).
 constexpr int kLdsLimitBytes = 160 * 1024;
 enum LdsSlot { kLdsForest = 0 /* 12 variants */, kLdsTreeWalk = 12, kLdsWide = 13 /* 3 operand modes */, kLdsFused = 16,
-               kLdsClassify = 17 /* 6 variants */ };
+               kLdsClassify = 17 /* 2 window depths x rows kept or not */ };
 #define SF_ALLOW_LDS(ctx, slot, func)                                                                         \
     do {                                                                                                      \
         if (!((ctx)->lds_ready & (1ull << (slot)))) {                                                         \

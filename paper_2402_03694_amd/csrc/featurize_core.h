@@ -22,6 +22,8 @@
 // (col[i * stride], stride = lanes that share the array, so every lane stays on its own bank).
 #pragma once
 
+#include <hip/hip_runtime.h>
+
 #include <cstdint>
 
 namespace sffeat {
