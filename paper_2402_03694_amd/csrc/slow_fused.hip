@@ -12,8 +12,11 @@
 // barrier inside a layer's K loop.  The last layer (at most 32 classes) runs on all eight waves
 // (four row blocks x two halves of K), followed by a per-row arg-max in registers and the
 // scatter of the label.
-// Blocks are persistent: each walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... up to the
-// device-side escalation count, so no block is launched for rows that do not exist.
+// Blocks are persistent.  The rows that exist (the device-side escalation count) are cut into
+// row blocks of 32 and dealt out evenly: every block gets a run of consecutive row blocks, the runs
+// differ by at most one, and a block walks its run in tiles of four row blocks; what is left at
+// the end of a run (one to three row blocks) is a last, lower tile (two row blocks high when that
+// is enough), so the blocks finish together and few rows fill the whole device.
 #include "mlp_common.h"
 
 namespace sf {
@@ -122,7 +125,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 
 constexpr int kWaves = 8;  // waves per block
 constexpr int kNI = 2;     // 32-column blocks per wave (64 columns)
-constexpr int kMI = 4;     // 32-row blocks per wave (all 128 rows)
+constexpr int kMI = 4;     // 32-row blocks per wave in a full tile (all 128 rows)
 constexpr int kRing = 4;   // weight operands of this many k-steps are in flight (K is padded to 16 * kRing)
 
 // The MFMA is issued with the WEIGHT operand first, so the 32x32 accumulator block holds the
@@ -133,8 +136,9 @@ constexpr int kRing = 4;   // weight operands of this many k-steps are in flight
 // The weight operands sit in a ring of kRing register buffers; a buffer is refilled for k-step
 // ks + kRing right after the MFMAs of k-step ks have been issued, so no load is waited for in the
 // step that issues it and no register is copied.  wbase is wave-uniform; lane_off = 16 * lane.
+template <int MI>
 __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const uint4* __restrict__ ws, uint32_t KS,
-                                          uint32_t nb0, uint32_t nb_total, uint32_t lane, f32x16 (&acc)[kMI][kNI])
+                                          uint32_t nb0, uint32_t nb_total, uint32_t lane, f32x16 (&acc)[MI][kNI])
 {
     if (nb0 >= nb_total) return; // this wave has no columns in this layer
     const uint16_t* arow = A + (lane & 31u) * lda + 8u * (lane >> 5);
@@ -158,22 +162,22 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
     // the activation operands are double-buffered too: those of k-step ks+1 are read from shared
     // memory before the MFMAs of k-step ks are issued (H has 8 columns of padding, so the read
     // one step past the end stays inside the row)
-    uint4 fa[2][kMI];
+    uint4 fa[2][MI];
 #pragma unroll
-    for (int i = 0; i < kMI; ++i) fa[0][i] = *reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda);
+    for (int i = 0; i < MI; ++i) fa[0][i] = *reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda);
     for (uint32_t k0 = 0; k0 < KS; k0 += kRing) {
 #pragma unroll
         for (int s = 0; s < kRing; ++s) {
             const uint32_t kn = k0 + s + 1u < KS ? k0 + s + 1u : k0 + s;
 #pragma unroll
-            for (int i = 0; i < kMI; ++i)
+            for (int i = 0; i < MI; ++i)
                 fa[(s + 1) & 1][i] = *reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda + kn * 16u);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < kNI; ++j) {
                 const bf16x8 b = as_frag(fb[s][j]);
 #pragma unroll
-                for (int i = 0; i < kMI; ++i)
+                for (int i = 0; i < MI; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, as_frag(fa[s & 1][i]), acc[i][j], 0, 0, 0);
             }
             // refill for k-step k0 + s + kRing; past the end this reads the next block (or the
@@ -191,7 +195,8 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
 // [n_valid, n_pad) inside the last real 32-column block come out as zeros by themselves (their weights and
 // bias entries are zero); a column block past the last real one (nb_total) holds a repeat of that block's
 // results in acc and is stored as zeros.
-__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kMI][kNI], uint32_t n0, uint32_t n_pad,
+template <int MI>
+__device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[MI][kNI], uint32_t n0, uint32_t n_pad,
                                              uint32_t nb_total, uint32_t lane)
 {
 #pragma unroll
@@ -202,7 +207,7 @@ __device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kM
             const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5); // first of 4 consecutive columns
             if (col < n_pad) {
 #pragma unroll
-                for (int i = 0; i < kMI; ++i) {
+                for (int i = 0; i < MI; ++i) {
                     const uint32_t row = i * 32u + (lane & 31u);
                     const float y0 = fmaxf(acc[i][j][4 * g + 0], 0.f), y1 = fmaxf(acc[i][j][4 * g + 1], 0.f);
                     const float y2 = fmaxf(acc[i][j][4 * g + 2], 0.f), y3 = fmaxf(acc[i][j][4 * g + 3], 0.f);
@@ -216,7 +221,8 @@ __device__ __forceinline__ void store_hidden(uint16_t* H, const f32x16 (&acc)[kM
 
 // accumulators start at the bias of their column (element v of lane l is column
 // 8*(v/4) + 4*(l/32) + v%4 of the 32-column block), so the epilogue has no add
-__device__ __forceinline__ void bias_acc(f32x16 (&acc)[kMI][kNI], const float* sbias, uint32_t n0, uint32_t lane)
+template <int MI>
+__device__ __forceinline__ void bias_acc(f32x16 (&acc)[MI][kNI], const float* sbias, uint32_t n0, uint32_t lane)
 {
 #pragma unroll
     for (int j = 0; j < kNI; ++j)
@@ -225,7 +231,7 @@ __device__ __forceinline__ void bias_acc(f32x16 (&acc)[kMI][kNI], const float* s
             const uint32_t col = n0 + j * 32u + 8u * g + 4u * (lane >> 5);
             const float4 b = col < (uint32_t)HMAX ? *reinterpret_cast<const float4*>(sbias + col) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int i = 0; i < kMI; ++i) {
+            for (int i = 0; i < MI; ++i) {
                 acc[i][j][4 * g + 0] = b.x;
                 acc[i][j][4 * g + 1] = b.y;
                 acc[i][j][4 * g + 2] = b.z;
@@ -278,65 +284,59 @@ __device__ __forceinline__ void store_chunk(bool has_map, const float* s_mu, con
         make_uint4(pack_bf16(z[0], z[1]), pack_bf16(z[2], z[3]), pack_bf16(z[4], z[5]), pack_bf16(z[6], z[7]));
 }
 
-// Tile schedule (one block, eight waves, persistent over tiles t, t + gridDim.x, ...):
+// Tile schedule of run_tiles (one block, eight waves, n_tiles consecutive tiles of MI row blocks):
 //   top        the input tile is written from registers that were loaded during the previous
 //              tile's last layer; the flow ids of the NEXT tile are requested
 //   layer 1    MFMA, then the next tile's flow ids are parked in shared memory, epilogue -> H
 //   layer 2    MFMA, epilogue -> H; the last layer's weight operands are requested
 //   layer 3    the next tile's feature rows are requested (they arrive while layer 3 runs);
-//              8 waves = 4 row blocks x 2 halves of K; halves are summed through shared memory
-__global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
+//              8 waves = MI row blocks x 2 halves of K (waves beyond that idle); halves are
+//              summed through shared memory
+// Rows from row_end on belong to another block (or do not exist): they read as zeros and nothing of
+// theirs is stored.
+struct FusedSmem {
+    uint16_t* H;      // [128][LDH]; also the input tile
+    uint32_t* s_flow; // [2][128]: this tile, next tile
+    float *s_b1, *s_b2, *s_b3, *s_part, *s_mu, *s_is;
+};
+
+template <int MI>
+__device__ __forceinline__ void run_tiles(const FusedArgs& a, const FusedSmem& m, uint32_t wave, uint32_t row_begin,
+                                          uint32_t n_tiles, uint32_t row_end)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* H = reinterpret_cast<uint16_t*>(smem);                              // [128][LDH]; also the input tile
-    uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)FBM * LDH * 2); // [2][128]: this tile, next tile
-    float* s_b1 = reinterpret_cast<float*>(s_flow + 2 * FBM);                      // [HMAX], zero past h1
-    float* s_b2 = s_b1 + HMAX;                                                     // [HMAX], zero past h2
-    float* s_b3 = s_b2 + HMAX;                                                     // [32], zero past c
-    float* s_part = s_b3 + 32;                                                     // [4][16][64] last-layer partial sums
-    float* s_mu = s_part + 4 * 16 * 64;                                            // [HMAX] input map (0 / 1 if none)
-    float* s_is = s_mu + HMAX;                                                     // [HMAX]
-    // the wave index is the same in every lane: say so, and everything derived from it (column
-    // block, weight pointers) lives in scalar registers
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint32_t total = *a.esc_count;
-    total = total < a.esc_cap ? total : a.esc_cap;
-    const uint32_t n_tiles = (total + FBM - 1) / FBM;
-    if (blockIdx.x >= n_tiles) return;
+    constexpr uint32_t TM = MI * 32u; // rows per tile
+    uint16_t* H = m.H;
+    uint32_t* s_flow = m.s_flow;
     const uint32_t k1p = up(a.n_in, kPadK), k2p = up(a.h1, kPadK), k3p = up(a.h2, kPadK);
     const uint32_t ldx = k1p + 8; // input tile row stride
     const uint32_t n0 = wave * 32u * kNI;
     const uint32_t nb1 = up(a.h1, 32) / 32u, nb2 = up(a.h2, 32) / 32u;
     const uint32_t chunks = k1p / 8u;
-    const bool in_regs = FBM * chunks <= (uint32_t)kXr * kWaves * 64u; // the whole input tile fits the threads' registers
-
-    for (uint32_t q = threadIdx.x; q < (uint32_t)HMAX; q += kWaves * 64u) {
-        s_b1[q] = q < a.h1 ? a.b1[q] : 0.f;
-        s_b2[q] = q < a.h2 ? a.b2[q] : 0.f;
-        if (q < 32u) s_b3[q] = q < a.c ? a.b3[q] : 0.f;
-        s_mu[q] = (a.mu && q < a.n_in) ? a.mu[q] : 0.f;
-        s_is[q] = (a.mu && q < a.n_in) ? a.inv_sigma[q] : 1.f;
-    }
+    const bool in_regs = TM * chunks <= (uint32_t)kXr * kWaves * 64u; // the whole input tile fits the threads' registers
     const bool has_map = a.mu != nullptr;
     float xr[kXr][8];
+    __syncthreads(); // the previous run of tiles (if any) is done with the tile and the flow ids
     {
         // first tile: flow ids and feature rows are fetched here, with nothing to overlap them
-        const uint32_t tid = threadIdx.x, row0 = blockIdx.x * FBM;
-        if (tid < FBM) s_flow[tid] = row0 + tid < total ? clamp_row(a.esc_idx[row0 + tid], a.n_rows) : kNoFlow;
+        // (the lane index behind an opaque barrier, as in the loop: nothing computed from it here is shared
+        // with, and kept alive across, another run of tiles)
+        uint32_t tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        if (tid < TM) s_flow[tid] = row_begin + tid < row_end ? clamp_row(a.esc_idx[row_begin + tid], a.n_rows) : kNoFlow;
         __syncthreads();
         if (in_regs) {
 #pragma unroll
             for (int u = 0; u < kXr; ++u) {
                 const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
-                load_chunk(a, r < (uint32_t)FBM ? s_flow[r] : kNoFlow, k, xr[u]);
+                load_chunk(a, r < TM ? s_flow[r] : kNoFlow, k, xr[u]);
             }
         }
     }
     uint32_t cur = 0;
-    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint32_t row0 = tile * FBM;
-        const uint32_t next_row0 = row0 + gridDim.x * FBM;
-        const bool has_next = tile + gridDim.x < n_tiles;
+    for (uint32_t ti = 0; ti < n_tiles; ++ti) {
+        const uint32_t row0 = row_begin + ti * TM;
+        const uint32_t next_row0 = row0 + TM;
+        const bool has_next = ti + 1u < n_tiles;
         // Re-read the lane index behind an opaque barrier in every tile: otherwise every per-lane
         // address of the tile body is hoisted out of this loop and spilled around the MFMA loops.
         uint32_t tid = threadIdx.x;
@@ -346,46 +346,49 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
         uint32_t* flow_next = s_flow + (cur ^ 1u) * FBM;
         // flow ids of the next tile: requested now, parked in shared memory after layer 1
         uint32_t nf = kNoFlow;
-        if (has_next && tid < FBM && next_row0 + tid < total) nf = clamp_row(a.esc_idx[next_row0 + tid], a.n_rows);
+        if (has_next && tid < TM && next_row0 + tid < row_end) nf = clamp_row(a.esc_idx[next_row0 + tid], a.n_rows);
         // input tile of this tile (H is free: the previous tile's last layer ended with a barrier)
         if (in_regs) {
 #pragma unroll
             for (int u = 0; u < kXr; ++u) {
                 const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
-                if (r < (uint32_t)FBM) store_chunk(has_map, s_mu, s_is, a.clamp, H + r * ldx + k, k, xr[u]);
+                if (r < TM) store_chunk(has_map, m.s_mu, m.s_is, a.clamp, H + r * ldx + k, k, xr[u]);
             }
         } else {
-            for (uint32_t g = tid; g < FBM * chunks; g += kWaves * 64u) {
+            for (uint32_t g = tid; g < TM * chunks; g += kWaves * 64u) {
                 const uint32_t r = g / chunks, k = (g - r * chunks) * 8u;
                 float z[8];
                 load_chunk(a, flow_cur[r], k, z);
-                store_chunk(has_map, s_mu, s_is, a.clamp, H + r * ldx + k, k, z);
+                store_chunk(has_map, m.s_mu, m.s_is, a.clamp, H + r * ldx + k, k, z);
             }
         }
         __syncthreads();
 
-        f32x16 acc[kMI][kNI];
+        f32x16 acc[MI][kNI];
         // layer 1
-        bias_acc(acc, s_b1, n0, lane);
-        wave_gemm(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc);
+        bias_acc<MI>(acc, m.s_b1, n0, lane);
+        wave_gemm<MI>(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc);
         __syncthreads(); // every wave has read the input tile; H may be overwritten
-        if (tid < FBM) flow_next[tid] = nf;
-        store_hidden(H, acc, n0, k2p, nb1, lane);
+        if (tid < TM) flow_next[tid] = nf;
+        store_hidden<MI>(H, acc, n0, k2p, nb1, lane);
         __syncthreads();
         // layer 2
-        bias_acc(acc, s_b2, n0, lane);
-        wave_gemm(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc);
+        bias_acc<MI>(acc, m.s_b2, n0, lane);
+        wave_gemm<MI>(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc);
         __syncthreads();
-        store_hidden(H, acc, n0, k3p, nb2, lane);
-        // layer 3: wave = (row block rb, half kh of K).  The hidden accumulators are dead, so a
-        // whole half-layer of weight operands fits in registers; they are requested before the
-        // barrier so that their latency overlaps it.
-        const uint32_t rb = wave & 3u, kh = wave >> 2;
-        const uint32_t KS3 = k3p / 16u, khalf = KS3 / 2u, kbeg = kh * khalf; // KS3 is a multiple of 4
+        store_hidden<MI>(H, acc, n0, k3p, nb2, lane);
+        // layer 3: wave = (row block rb, half kh of K); waves beyond MI x 2 only keep the barriers.  The hidden
+        // accumulators are dead, so a whole half-layer of weight operands fits in registers; they are requested
+        // before the barrier so that their latency overlaps it.
+        const uint32_t rb = wave % (uint32_t)MI, kh = wave / (uint32_t)MI;
+        const bool l3 = MI == kMI ? true : kh < 2u; // (eight waves: with four row blocks every wave has a share)
+        const uint32_t KS3 = k3p / 16u, khalf = KS3 / 2u, kbeg = (l3 ? kh : 0u) * khalf; // KS3 is a multiple of 4
         uint4 wv[16];
+        if (l3) {
 #pragma unroll
-        for (int s3 = 0; s3 < 16; ++s3)
-            wv[s3] = a.w3s[(size_t)(kbeg + ((uint32_t)s3 < khalf ? (uint32_t)s3 : khalf - 1u)) * 64u + lane];
+            for (int s3 = 0; s3 < 16; ++s3)
+                wv[s3] = a.w3s[(size_t)(kbeg + ((uint32_t)s3 < khalf ? (uint32_t)s3 : khalf - 1u)) * 64u + lane];
+        }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         // the next tile's feature rows: requested now, consumed at the top of the next iteration
@@ -393,7 +396,7 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
 #pragma unroll
             for (int u = 0; u < kXr; ++u) {
                 const uint32_t g = tid + u * kWaves * 64u, r = g / chunks, k = (g - r * chunks) * 8u;
-                load_chunk(a, r < (uint32_t)FBM ? flow_next[r] : kNoFlow, k, xr[u]);
+                load_chunk(a, r < TM ? flow_next[r] : kNoFlow, k, xr[u]);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -402,41 +405,43 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) c3[v] = c3b[v] = 0.f;
             const uint16_t* arow = H + (rb * 32u + (lane & 31u)) * LDH + 8u * (lane >> 5);
-            for (uint32_t kb = 0; kb < khalf; kb += 16u) {
-                if (kb) {
+            if (l3) {
+                for (uint32_t kb = 0; kb < khalf; kb += 16u) {
+                    if (kb) {
 #pragma unroll
-                    for (int s3 = 0; s3 < 16; ++s3)
-                        wv[s3] = a.w3s[(size_t)(kbeg + (kb + s3 < khalf ? kb + s3 : khalf - 1u)) * 64u + lane];
-                }
+                        for (int s3 = 0; s3 < 16; ++s3)
+                            wv[s3] = a.w3s[(size_t)(kbeg + (kb + s3 < khalf ? kb + s3 : khalf - 1u)) * 64u + lane];
+                    }
 #pragma unroll
-                for (int s3 = 0; s3 < 16; s3 += 2) {
-                    if (kb + s3 < khalf)
-                        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            as_frag(wv[s3]), as_frag(*reinterpret_cast<const uint4*>(arow + (kbeg + kb + s3) * 16u)), c3, 0, 0, 0);
-                    if (kb + s3 + 1 < khalf)
-                        c3b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            as_frag(wv[s3 + 1]), as_frag(*reinterpret_cast<const uint4*>(arow + (kbeg + kb + s3 + 1) * 16u)), c3b, 0, 0, 0);
+                    for (int s3 = 0; s3 < 16; s3 += 2) {
+                        if (kb + s3 < khalf)
+                            c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                as_frag(wv[s3]), as_frag(*reinterpret_cast<const uint4*>(arow + (kbeg + kb + s3) * 16u)), c3, 0, 0, 0);
+                        if (kb + s3 + 1 < khalf)
+                            c3b = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                as_frag(wv[s3 + 1]), as_frag(*reinterpret_cast<const uint4*>(arow + (kbeg + kb + s3 + 1) * 16u)), c3b, 0, 0, 0);
+                    }
                 }
             }
 #pragma unroll
             for (int v = 0; v < 16; ++v) c3[v] += c3b[v];
-            float* part = s_part + rb * (16 * 64);
-            if (kh == 1u) {
+            float* part = m.s_part + rb * (16 * 64);
+            if (l3 && kh == 1u) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) part[v * 64 + lane] = c3[v];
             }
             __syncthreads(); // also: every wave is done reading H
-            if (kh == 0u) {
+            if (l3 && kh == 0u) {
                 // the accumulator is transposed: lane l holds 16 classes of row l%32, lane l^32 the others
                 const uint32_t r = rb * 32u + (lane & 31u);
-                const bool row_ok = row0 + r < total;
+                const bool row_ok = row0 + r < row_end;
                 uint32_t best = kNoFlow;
                 float bv = 0.f;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const uint32_t c = 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3); // ascending in v
                     if (c < a.c) {
-                        const float y = c3[v] + part[v * 64 + lane] + s_b3[c];
+                        const float y = c3[v] + part[v * 64 + lane] + m.s_b3[c];
                         if (a.logits && row_ok) a.logits[(size_t)(row0 + r) * a.c + c] = y;
                         if (best == kNoFlow || y > bv) {
                             bv = y;
@@ -456,6 +461,48 @@ __global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
         }
         cur ^= 1u;
     }
+}
+
+__global__ __launch_bounds__(kWaves * 64) void mlp_fused(FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    FusedSmem m;
+    m.H = reinterpret_cast<uint16_t*>(smem);                                    // [128][LDH]; also the input tile
+    m.s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)FBM * LDH * 2);       // [2][128]: this tile, next tile
+    m.s_b1 = reinterpret_cast<float*>(m.s_flow + 2 * FBM);                      // [HMAX], zero past h1
+    m.s_b2 = m.s_b1 + HMAX;                                                     // [HMAX], zero past h2
+    m.s_b3 = m.s_b2 + HMAX;                                                     // [32], zero past c
+    m.s_part = m.s_b3 + 32;                                                     // [4][16][64] last-layer partial sums
+    m.s_mu = m.s_part + 4 * 16 * 64;                                            // [HMAX] input map (0 / 1 if none)
+    m.s_is = m.s_mu + HMAX;                                                     // [HMAX]
+    // the wave index is the same in every lane: say so, and everything derived from it (column
+    // block, weight pointers) lives in scalar registers
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t total = *a.esc_count;
+    total = total < a.esc_cap ? total : a.esc_cap;
+    // this block's run of row blocks: the runs of the grid differ by at most one row block
+    const uint32_t rb_total = (total + 31u) / 32u;
+    const uint32_t rb_lo = rb_total / gridDim.x, rb_rem = rb_total % gridDim.x;
+    const uint32_t rb_first = blockIdx.x * rb_lo + (blockIdx.x < rb_rem ? blockIdx.x : rb_rem);
+    const uint32_t rb_count = rb_lo + (blockIdx.x < rb_rem ? 1u : 0u);
+    if (rb_count == 0) return;
+    const uint32_t row_begin = rb_first * 32u;
+    uint32_t row_end = (rb_first + rb_count) * 32u;
+    row_end = row_end < total ? row_end : total;
+
+    for (uint32_t q = threadIdx.x; q < (uint32_t)HMAX; q += kWaves * 64u) {
+        m.s_b1[q] = q < a.h1 ? a.b1[q] : 0.f;
+        m.s_b2[q] = q < a.h2 ? a.b2[q] : 0.f;
+        if (q < 32u) m.s_b3[q] = q < a.c ? a.b3[q] : 0.f;
+        m.s_mu[q] = (a.mu && q < a.n_in) ? a.mu[q] : 0.f;
+        m.s_is[q] = (a.mu && q < a.n_in) ? a.inv_sigma[q] : 1.f;
+    }
+    // full tiles of four row blocks, then what is left: three row blocks run as a (masked) full tile, one or
+    // two as a tile of half the height
+    const uint32_t rest = rb_count % (uint32_t)kMI;
+    const uint32_t n_full = rb_count / (uint32_t)kMI + (rest == 3u ? 1u : 0u);
+    if (n_full) run_tiles<kMI>(a, m, wave, row_begin, n_full, row_end);
+    if (rest == 1u || rest == 2u) run_tiles<2>(a, m, wave, row_begin + n_full * FBM, 1u, row_end);
 }
 
 constexpr size_t kFusedLds = (size_t)FBM * LDH * 2 + 2 * FBM * 4 + (4 * HMAX + 32) * 4 + 4 * 16 * 64 * 4;
@@ -556,9 +603,9 @@ int slow_fused(sf_ctx* ctx, void* ws, bool ws_is_ordered, const float* feat, uin
     a.logits = logits;
     a.labels = labels;
     SF_ALLOW_LDS(ctx, sf::kLdsFused, mlp_fused);
-    uint32_t tiles_cap = (esc_cap + FBM - 1) / FBM;
+    const uint32_t rb_cap = (esc_cap + 31u) / 32u;
     uint32_t grid = (uint32_t)ctx->n_cu; // one block per compute unit (its shared memory fills the unit)
-    if (grid > tiles_cap) grid = tiles_cap;
+    if (grid > rb_cap) grid = rb_cap;
     if (grid == 0) grid = 1;
     mlp_fused<<<grid, kWaves * 64, kFusedLds, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "mlp_fused");
