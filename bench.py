@@ -85,6 +85,25 @@ def gather_probe(ctx, dev):
     return out
 
 
+def copy_bandwidth(dev):
+    """What a plain device-to-device copy of 256 MiB reaches on this device (bytes read + bytes written per second,
+    in GB/s): the practical ceiling next to the published HBM peak the rooflines are priced at."""
+    import torch
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    for i in range(5):
+        ev[i].record()
+        dst.copy_(src)
+    ev[5].record()
+    torch.cuda.synchronize()
+    ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
+    return 2.0 * (256 << 20) / (ms * 1e-3) / 1e9
+
+
 def algorithmic_bytes(cfg, n_flows, n_pkts, esc_frac):
     """Bytes the method itself must move per call (inputs read once + outputs written once)."""
     F = cfg.n_features
@@ -235,13 +254,13 @@ def three_tier(args, cfg):
     for i, nm in enumerate(names[:5]):
         a = bytes_[i] / (avg[i] * 1e-3) / 1e9
         kernels[nm] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
-                       "traffic": None, "ms": float(avg[i]), "bytes": bytes_[i]}
+                       "traffic": measured_traffic(nm, args.config, n), "ms": float(avg[i]), "bytes": bytes_[i]}
     visits = float(n1) * cfg.n_trees * cfg.tree_depth
     kernels["sf_fast_infer_subset"].update(node_visits=visits, visits_per_s=visits / (avg[3] * 1e-3))
     tf = mlp_flops(cfg, n2) / (avg[5] * 1e-3) / 1e12
     kernels["sf_slow_infer"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "ms": float(avg[5]),
-                                "flops": mlp_flops(cfg, n2)}
+                                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic("sf_slow_infer", args.config, n),
+                                "ms": float(avg[5]), "flops": mlp_flops(cfg, n2)}
     dominant = names[int(np.argmax(avg))]
     roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
     roof["kernel"] = dominant
@@ -405,7 +424,7 @@ class TwoTier:
             ev[1].record()
         if self.fused:
             ctx.sf_featurize_fast_infer(d_pk, cfg.depths, self.d_model, vmin, None if cfg.raw_pkts else self.feat, self.pred,
-                                        self.top)
+                                        self.top, labels=self.labels)    # labels start as the fast prediction
         elif self.gbdt:
             ctx.sf_gbdt_infer(self.feat, self.d_model, self.kind, self.pred, self.score, n_flows=n)
         else:
@@ -418,12 +437,12 @@ class TwoTier:
             ctx.sf_route(self.top, self.pred, vmin, self.esc_idx, self.esc_count, n_flows=n)
         if ev:
             ev[3].record()
+        pred = None if self.fused else self.pred
         if cfg.raw_pkts:
             ctx.sf_slow_infer(self.d_mlp, self.esc_idx, self.esc_count, self.labels, raw_src=d_pk, raw_pkts=cfg.raw_pkts,
-                              raw_bits=cfg.raw_bits, esc_cap=n, pred=self.pred)
+                              raw_bits=cfg.raw_bits, esc_cap=n, pred=pred)
         else:
-            ctx.sf_slow_infer(self.d_mlp, self.esc_idx, self.esc_count, self.labels, feat=self.feat, esc_cap=n,
-                              pred=self.pred)
+            ctx.sf_slow_infer(self.d_mlp, self.esc_idx, self.esc_count, self.labels, feat=self.feat, esc_cap=n, pred=pred)
         if ev:
             ev[4].record()
 
@@ -649,6 +668,13 @@ def sweep_bench(args, cfg):
         n_esc = int(tt.esc_count.cpu().numpy().view(np.uint32)[0])
         out = result_line(tt, args, args.config, vmin, how, n, tt.pk.n_pkts, n_esc, args.steps, wall, call_ms, probe,
                           {"target_fraction": target})
+        if abs(target - 0.25) > 1e-9:
+            # the counter runs behind the traffic table were taken at the middle target: what depends on the
+            # escalated portion is not known for the others
+            for k in ("sf_route", "sf_slow_infer"):
+                out["kernels"][k]["traffic"] = None
+            if out["roofline"]["kernel"] in ("sf_route", "sf_slow_infer"):
+                out["roofline"]["traffic"] = None
         if not args.no_cpu_baseline and i == len(targets) // 2:
             out["cpu_baseline"] = cpu_baseline(cfg, n, vmin, n_esc / n)
         print(json.dumps(out), flush=True)
@@ -673,6 +699,8 @@ def main():
                          "for the headline workload (whose shape the fused kernel covers), with the separate calls timed "
                          "beside it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="time the main step only (no separate-calls leg, no universal-gate leg): for profiler runs")
     ap.add_argument("--join", action="store_true", help="time the queue join in front of the slow model instead")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for HBM byte counters)")
@@ -695,6 +723,12 @@ def main():
         args.steps = cfg.n_batches if cfg.n_batches > 1 else 20
     if args.gate == "auto":
         args.gate = "per-class" if args.config == 2 else "universal"
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)              # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     if args.join:
         return join_bench(args)
     if cfg.tree0_depth:
@@ -717,19 +751,14 @@ def main():
         n_esc0 = int(tt.esc_count.cpu().numpy().view(np.uint32)[0])
         if cfg.raw_pkts == 0 and rows_written != n_esc0:
             tt.fused = False        # this shape ran the separate kernels inside the library
-    if args.copy_probe:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        dst.copy_(src)              # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
     probe = gather_probe(tt.ctx, dev)
     wall, call_ms = timed_steps(tt, vmin, args.steps, args.warmup)
     n_esc = int(tt.esc_count.cpu().numpy().view(np.uint32)[0])
     out = result_line(tt, args, args.config, vmin, how, n, tt.pk.n_pkts, n_esc, args.steps, wall, call_ms, probe)
+    out["measured_copy_GBps"] = copy_bandwidth(dev)
     out["config"]["calls"] = "sf_featurize_fast_infer + sf_route + sf_slow_infer" if tt.fused else \
                              "sf_featurize + sf_fast_infer + sf_route + sf_slow_infer"
-    if tt.fused:
+    if tt.fused and not args.no_extras:
         # the same step through the four separate calls
         tt.fused = False
         s_wall, s_ms = timed_steps(tt, vmin, args.steps, args.warmup)
@@ -739,7 +768,7 @@ def main():
         out["separate_calls"] = {"value": n * args.steps / s_wall, "unit": "flows/s", "ms_per_step": s_wall * 1e3 / args.steps,
                                  "kernels": s_kernels}
         tt.fused = True
-    if args.gate == "per-class" and not tt.gbdt:
+    if args.gate == "per-class" and not tt.gbdt and not args.no_extras:
         # the same workload behind one threshold for all classes: the integer score then reaches only a few portions
         u_vmin, reached = tt.sf.sf_vmin_for_target(tt.hist, cfg.n_trees, args.target if args.target >= 0 else cfg.target_fracs[0])
         u_wall, u_ms = timed_steps(tt, u_vmin, args.steps, args.warmup)

@@ -416,7 +416,9 @@ int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32
  * then written only where the slow model will read it: row i of feat is written iff flow i escalates under
  * the gate given by host_vmin / n_vmin (as sf_route: top_votes < vmin, or vmin[pred]); the other rows are
  * left untouched.  feat = NULL: no row is written (a slow model that reads header bits needs none).
- * Other shapes run the separate kernels and write every row (they need feat).
+ * Other shapes run the separate kernels and write every row (they need feat).  labels: optional
+ * [n_flows]; labels[i] = pred[i], the start of the final label array (pass it to sf_slow_infer with
+ * pred = NULL).
  *
  * sf_classify: all four steps: sf_featurize_fast_infer, sf_route, sf_slow_infer (with pred given and
  * esc_cap = n_flows); the results are those of the four calls in turn with the same arguments, except for
@@ -425,7 +427,7 @@ int sf_slow_infer_pairs(sf_ctx* ctx, const float* feat, uint32_t feat_ld, uint32
  * row e belongs to flow esc_idx[e].  Both use workspace as the separate calls do. */
 int sf_featurize_fast_infer(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
                             const uint16_t* host_vmin, uint32_t n_vmin, float* feat, uint32_t feat_ld,
-                            uint16_t* pred, uint16_t* top_votes);
+                            uint16_t* pred, uint16_t* top_votes, uint16_t* labels);
 int sf_classify(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
                 const uint16_t* host_vmin, uint32_t n_vmin, const sf_mlp* mlp, float* feat, uint32_t feat_ld,
                 uint16_t* pred, uint16_t* top_votes, uint32_t* esc_idx, uint32_t* esc_count, float* logits,

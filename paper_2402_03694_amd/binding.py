@@ -112,7 +112,7 @@ def load_library() -> ctypes.CDLL:
                                 ctypes.POINTER(ctypes.c_uint16), u32, ctypes.POINTER(SfMlp), vp, u32, vp, vp, vp, vp, vp, vp]
     lib.sf_featurize_fast_infer.restype = ctypes.c_int
     lib.sf_featurize_fast_infer.argtypes = [vp, ctypes.POINTER(SfPackets), ctypes.POINTER(SfFeatCfg), ctypes.POINTER(SfForest),
-                                            ctypes.POINTER(ctypes.c_uint16), u32, vp, u32, vp, vp]
+                                            ctypes.POINTER(ctypes.c_uint16), u32, vp, u32, vp, vp, vp]
     lib.sf_probe_gather.restype = ctypes.c_int
     lib.sf_probe_gather.argtypes = [vp, ctypes.c_int, u32, u32, u32, vp, vp, ctypes.POINTER(ctypes.c_uint64)]
     lib.sf_vmin_from_theta.restype = u32
@@ -427,13 +427,15 @@ class ServeFlow:
                                        _ptr(esc_idx, torch.int32), _ptr(esc_count, torch.int32)))
 
     def sf_featurize_fast_infer(self, pk: DevicePackets, depths: Sequence[int], forest: DeviceForest, vmin,
-                                feat: Optional[torch.Tensor], pred: torch.Tensor, top_votes: torch.Tensor):
+                                feat: Optional[torch.Tensor], pred: torch.Tensor, top_votes: torch.Tensor,
+                                labels: Optional[torch.Tensor] = None):
         s, c, f = pk.c_struct(), _feat_cfg(depths), forest.c_struct()
         vm = [int(vmin)] if isinstance(vmin, int) else [int(v) for v in vmin]
         arr = (ctypes.c_uint16 * len(vm))(*vm)
         self._check(self._lib.sf_featurize_fast_infer(
             self._h, ctypes.byref(s), ctypes.byref(c), ctypes.byref(f), arr, len(vm), _ptr(feat, torch.float32),
-            int(feat.shape[1]) if feat is not None else 0, _ptr(pred, torch.int16), _ptr(top_votes, torch.int16)))
+            int(feat.shape[1]) if feat is not None else 0, _ptr(pred, torch.int16), _ptr(top_votes, torch.int16),
+            _ptr(labels, torch.int16)))
 
     def sf_classify(self, pk: DevicePackets, depths: Sequence[int], forest: DeviceForest, vmin, mlp: DeviceMlp,
                     feat: Optional[torch.Tensor], pred: torch.Tensor, top_votes: torch.Tensor, esc_idx: torch.Tensor,

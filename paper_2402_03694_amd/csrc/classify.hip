@@ -130,7 +130,7 @@ int launch_fused(sf_ctx* ctx, const ClassifyArgs& c, size_t lds, int slot)
 // steps 1-3 for both entry points; keep_rows: feature rows of the flows the gate hands on are wanted
 int run_features_and_forest(sf_ctx* ctx, const char* who, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
                             const uint16_t* host_vmin, uint32_t n_vmin, bool keep_rows, float* feat, uint32_t feat_ld,
-                            uint16_t* pred, uint16_t* top_votes)
+                            uint16_t* pred, uint16_t* top_votes, uint16_t* labels, bool* labels_done)
 {
     if (!pk || !cfg || !forest) return sf::fail(ctx, SF_EINVAL, "%s: packets, config or forest is NULL", who);
     if (!host_vmin || n_vmin < 1 || n_vmin > SF_MAX_CLASSES)
@@ -148,6 +148,7 @@ int run_features_and_forest(sf_ctx* ctx, const char* who, const sf_packets* pk, 
         return sf::fail(ctx, SF_EINVAL, "%s: the forest splits on %u features, the windows give %u", who, forest->n_features, F);
     if (pk->n_pkts >> 32) return sf::fail(ctx, SF_EINVAL, "%s: n_pkts exceeds 32-bit offsets", who);
     const uint32_t n = pk->n_flows;
+    *labels_done = false;
     if (n == 0) return SF_OK;
     if (!pk->flow_off || !pred || !top_votes || (keep_rows && !feat))
         return sf::fail(ctx, SF_EINVAL, "%s: flow_off, feat, pred or top_votes is NULL", who);
@@ -188,6 +189,8 @@ int run_features_and_forest(sf_ctx* ctx, const char* who, const sf_packets* pk, 
     c.fa.n_rows = n;
     c.fa.pred = pred;
     c.fa.top = top_votes;
+    c.fa.labels = labels; // the label array starts as the fast prediction (Section 4.4); the slow model overwrites its flows
+    *labels_done = labels != nullptr;
     c.fa.feat_out = feat;
     c.fa.feat_out_ld = feat_ld;
     c.fa.feat_out16 = ((uintptr_t)feat & 15u) == 0 && (feat_ld & 3u) == 0;
@@ -201,13 +204,27 @@ int run_features_and_forest(sf_ctx* ctx, const char* who, const sf_packets* pk, 
 
 } // namespace
 
+namespace {
+// labels = pred for every flow (the separate kernels do not write labels: one small copy)
+__global__ __launch_bounds__(256) void labels_from_pred(const uint16_t* __restrict__ pred, uint16_t* __restrict__ labels, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) labels[i] = pred[i];
+}
+} // namespace
+
 extern "C" int sf_featurize_fast_infer(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
                                        const uint16_t* host_vmin, uint32_t n_vmin, float* feat, uint32_t feat_ld,
-                                       uint16_t* pred, uint16_t* top_votes)
+                                       uint16_t* pred, uint16_t* top_votes, uint16_t* labels)
 {
     if (!ctx) return sf::fail(nullptr, SF_EINVAL, "sf_featurize_fast_infer: ctx is NULL");
-    return run_features_and_forest(ctx, "sf_featurize_fast_infer", pk, cfg, forest, host_vmin, n_vmin, feat != nullptr, feat, feat_ld,
-                                   pred, top_votes);
+    bool done = false;
+    const int rc = run_features_and_forest(ctx, "sf_featurize_fast_infer", pk, cfg, forest, host_vmin, n_vmin, feat != nullptr, feat,
+                                           feat_ld, pred, top_votes, labels, &done);
+    if (rc != SF_OK || !labels || done || !pk || pk->n_flows == 0) return rc;
+    uint32_t blocks = (pk->n_flows + 255u) / 256u;
+    labels_from_pred<<<blocks > 4096u ? 4096u : blocks, 256, 0, ctx->stream>>>(pred, labels, pk->n_flows);
+    SF_LAUNCH_CHECK(ctx, "labels_from_pred");
+    return SF_OK;
 }
 
 extern "C" int sf_classify(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg* cfg, const sf_forest* forest,
@@ -221,10 +238,12 @@ extern "C" int sf_classify(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg*
     const bool raw = cfg->raw_pkts > 0;
     const uint32_t n = pk->n_flows;
     if (n && (!esc_idx || !labels)) return sf::fail(ctx, SF_EINVAL, "sf_classify: esc_idx or labels is NULL");
-    int rc = run_features_and_forest(ctx, "sf_classify", pk, cfg, forest, host_vmin, n_vmin, !raw, feat, feat_ld, pred, top_votes);
+    bool labels_done = false;
+    int rc = run_features_and_forest(ctx, "sf_classify", pk, cfg, forest, host_vmin, n_vmin, !raw, feat, feat_ld, pred, top_votes,
+                                     labels, &labels_done);
     if (rc != SF_OK) return rc;
     rc = sf_route(ctx, top_votes, pred, n, host_vmin, n_vmin, esc_idx, esc_count);
     if (rc != SF_OK || n == 0) return rc;
     return sf_slow_infer(ctx, raw ? nullptr : feat, raw ? 0u : feat_ld, raw ? pk : nullptr, raw ? cfg : nullptr, esc_idx, esc_count, n,
-                         n, mlp, pred, logits, labels);
+                         n, mlp, labels_done ? nullptr : pred, logits, labels);
 }

@@ -129,6 +129,34 @@ def test_shapes_that_run_the_separate_kernels(cfg_id, n, vmin):
     assert _check(cfg, pk, forest, mlp, vmin, fused=False) > 0
 
 
+@pytest.mark.parametrize("cfg_id,n", [(2, 3000 + 7), (4, 2000 + 3)])
+def test_steps_one_to_three_alone(cfg_id, n):
+    """sf_featurize_fast_infer by itself (fused for the first shape, separate kernels inside for the second):
+    pred, top_votes, labels = pred, and the rows of the flows below the threshold."""
+    import torch
+    import paper_2402_03694_amd as sf
+    cfg = synth.get_config(cfg_id)
+    pk = synth.make_packets(cfg, n_flows=n)
+    forest, _ = _models(cfg, pk)
+    o_feat, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=8)
+    _, o_pred, o_top, _ = oracle.fast_infer(o_feat, forest, want_votes=False, n_threads=8)
+    vmin = 15 if cfg_id == 2 else 19
+    dev = "cuda:0"
+    ctx = sf.ServeFlow(sf.sf_workspace_bytes(n, forest.n_trees, forest.depth))
+    d_pk, d_forest = sf.packets_to_device(pk, dev), sf.forest_to_device(forest, dev)
+    feat = torch.full((n, cfg.n_features), SENTINEL, dtype=torch.float32, device=dev)
+    pred, top, labels = (torch.full((n,), -1, dtype=torch.int16, device=dev) for _ in range(3))
+    ctx.sf_featurize_fast_infer(d_pk, cfg.depths, d_forest, vmin, feat, pred, top, labels=labels)
+    torch.cuda.synchronize()
+    u16 = lambda t: t.cpu().numpy().view(np.uint16)
+    assert np.array_equal(u16(pred), o_pred) and np.array_equal(u16(top), o_top) and np.array_equal(u16(labels), o_pred)
+    esc = o_top < vmin
+    g = feat.cpu().numpy()
+    assert np.array_equal(g[esc].view(np.uint32), o_feat[esc].view(np.uint32))
+    if cfg_id == 2:
+        assert np.all(g[~esc] == SENTINEL)
+
+
 def test_classify_errors_and_no_flows():
     import torch
     import paper_2402_03694_amd as sf
