@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void pack_forest(uint32_t n_trees, uint32_t de
         p.thr0 = thr[0];
         p.thr1 = thr[1];
         p.thr2 = thr[2];
-        p.feats = fe[0] | (fe[1] << 8) | (fe[2] << 16);
+        p.feats = pack_feats(fe[0], fe[1], fe[2]);
         out[g] = p;
     }
 }

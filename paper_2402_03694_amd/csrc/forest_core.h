@@ -18,10 +18,18 @@
 
 namespace sfforest {
 
+constexpr uint32_t kFeatRot = 10; // the word of feature indices is rotated left by this (see forest_walk)
+
 struct __align__(16) PairRec {
     float thr0, thr1, thr2; // node, its left child, its right child
-    uint32_t feats;         // bits 0..7, 8..15, 16..23: their feature indices
+    uint32_t feats;         // their feature indices as 8-bit fields (f0 | f1 << 8 | f2 << 16), rotated left by kFeatRot
 };
+
+__host__ __device__ inline uint32_t pack_feats(uint32_t f0, uint32_t f1, uint32_t f2)
+{
+    const uint32_t w = f0 | (f1 << 8) | (f2 << 16);
+    return (w << kFeatRot) | (w >> (32u - kFeatRot));
+}
 
 __host__ __device__ inline uint32_t pair_levels(uint32_t depth) { return (depth + 1u) / 2u; }
 __host__ __device__ inline uint32_t recs_upto(uint32_t j) { return ((1u << (2u * j)) - 1u) / 3u; } // (4^j-1)/3
@@ -109,32 +117,48 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
     const uint32_t full_pairs = depth >> 1;
     const uint32_t lds_pairs = a.top_pairs < full_pairs ? a.top_pairs : full_pairs;
     const bool odd = depth & 1u;
-    const char* xlane = reinterpret_cast<const char*>(xT) + slot * 4u; // the flow's column
+    // The tile is read through absolute shared-memory addresses formed with bit operations: it heads the
+    // block's shared memory, which in the kernels that use this walk is dynamic only, so the tile starts at
+    // address 0 and "offset of the feature's row | offset of the flow's column" is the address.
+    typedef __attribute__((address_space(3))) const float LdsFloat;
+    const uint32_t tile_abs = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(xT);
+    const uint32_t xl = tile_abs + slot * 4u; // address of the flow's column in the tile's first row
     uint32_t* vcol = vT + slot;
     const uint32_t rec_bytes = n_rec * 16u, top_bytes = top_recs * 16u;
     const uint32_t leaf_base = recs_upto(full_pairs); // record index of position 0 on tree level 2*full_pairs
     const uint32_t n_leaf = 1u << depth;
 
+    // The three feature indices of a record sit in its last word as 8-bit fields, rotated so that the first
+    // stands at bits 10..17: for a tile of 256 flows (a feature's row is 1024 bytes) masking the word gives
+    // the byte offset of x[feature] in one operation, and a rotation by 8 or 16 bits brings a child's field
+    // there.  Narrower tiles (two or four lanes per flow) rotate by one or two bits more.
+    constexpr uint32_t kFieldMask = 0xFFu << kColShift;
+    constexpr uint32_t kRot0 = kFeatRot - kColShift;
+#define SF_FEAT_ROT(FW, SH) (*(LdsFloat*)(uintptr_t)((__builtin_amdgcn_alignbit((FW), (FW), (SH)) & kFieldMask) | xl))
+#define SF_FEAT_0(FW) (kRot0 == 0u ? *(LdsFloat*)(uintptr_t)(((FW) & kFieldMask) | xl) : SF_FEAT_ROT(FW, kRot0))
+
     // two visits from one record; o is the byte offset of the record inside its tree.
     // One lane per flow (S = 1, eight or more waves per compute unit): the child's feature is fetched
     // after the parent's test (two shared-memory reads per record, the second dependent on the first):
     // the shared-memory pipe is the scarcer resource there and the resident waves cover the latency.
+    // The record offset moves on as 4 * o + 16 * (1 + 2 * right0 + right1) = ((o + sh) << 2) - 16 + 16 * right1
+    // with sh = 8 or 16, the rotation that selects the child's feature field.
     // Lanes sharing a flow (S = 2: forests whose shared-memory needs leave few waves resident): all
     // three features up front (three independent reads), which is faster when latency binds.
 #define SF_PAIR_STEP(REC, O)                                                                              \
     do {                                                                                                  \
         const uint32_t fw = (REC).w;                                                                      \
-        const float x0 = *reinterpret_cast<const float*>(xlane + ((fw & 0xFFu) << kColShift));            \
+        const float x0 = SF_FEAT_0(fw);                                                                   \
         const bool r0 = !(x0 <= __uint_as_float((REC).x));                                                \
         if (S == 1) {                                                                                     \
-            const uint32_t fc = r0 ? (fw >> 16) : ((fw >> 8) & 0xFFu);                                    \
+            const uint32_t sh = r0 ? 16u : 8u;                                                            \
             const float tc = __uint_as_float(r0 ? (REC).z : (REC).y);                                     \
-            const float xc = *reinterpret_cast<const float*>(xlane + (fc << kColShift));                  \
+            const float xc = SF_FEAT_ROT(fw, sh + kRot0);                                                 \
             const bool rc = !(xc <= tc);                                                                  \
-            (O) = 4u * (O) + (r0 ? 48u : 16u) + (rc ? 16u : 0u);                                          \
+            (O) = (((O) + sh) << 2) + (rc ? 0u : 0xFFFFFFF0u);                                            \
         } else {                                                                                          \
-            const float x1 = *reinterpret_cast<const float*>(xlane + (((fw >> 8) & 0xFFu) << kColShift)); \
-            const float x2 = *reinterpret_cast<const float*>(xlane + ((fw >> 16) << kColShift));          \
+            const float x1 = SF_FEAT_ROT(fw, kRot0 + 8u);                                                 \
+            const float x2 = SF_FEAT_ROT(fw, kRot0 + 16u);                                                \
             const bool r1 = !(x1 <= __uint_as_float((REC).y));                                            \
             const bool r2 = !(x2 <= __uint_as_float((REC).z));                                            \
             const uint32_t inc_l = r1 ? 32u : 16u, inc_r = r2 ? 64u : 48u;                                \
@@ -182,7 +206,7 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
                 rec[u] = *reinterpret_cast<const uint4*>(gb + (size_t)tt[u] * rec_bytes + o[u]);
 #pragma unroll
             for (int u = 0; u < kIlp; ++u) {
-                const float x0 = *reinterpret_cast<const float*>(xlane + ((rec[u].w & 0xFFu) << kColShift));
+                const float x0 = SF_FEAT_0(rec[u].w);
                 const bool r0 = !(x0 <= __uint_as_float(rec[u].x));
                 leaf[u] = 2u * ((o[u] >> 4) - leaf_base) + (r0 ? 1u : 0u);
             }
@@ -218,6 +242,8 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
         }
     }
 #undef SF_PAIR_STEP
+#undef SF_FEAT_0
+#undef SF_FEAT_ROT
     if (S > 1) __syncthreads(); // all lanes of a flow have added their votes before its first lane reads them
     if (!live || grp != 0) return;
     if (GBDT) {
