@@ -128,6 +128,23 @@ constexpr int kNI = 2;     // 32-column blocks per wave (64 columns)
 constexpr int kMI = 4;     // 32-row blocks per wave in a full tile (all 128 rows)
 constexpr int kRing = 4;   // weight operands of this many k-steps are in flight (K is padded to 16 * kRing)
 
+// first kRing k-steps of a wave's weight operands (column blocks nb0 .. nb0+kNI, clamped to the last real one)
+__device__ __forceinline__ void ring_fill(uint4 (&fb)[kRing][kNI], const uint4* __restrict__ ws, uint32_t KS, uint32_t nb0,
+                                          uint32_t nb_total, uint32_t lane)
+{
+#pragma unroll
+    for (int s = 0; s < kRing; ++s) {
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) {
+            const uint32_t nb = nb0 + j < nb_total ? nb0 + j : nb_total - 1u;
+            fb[s][j] = ws[((size_t)nb * KS + s) * 64u + lane];
+        }
+        // ring order: the counter wait in front of an MFMA is placed for the worst order on any path
+        // into the loop, and a fill issued out of order makes every k-step wait for the newest load
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // The MFMA is issued with the WEIGHT operand first, so the 32x32 accumulator block holds the
 // output transposed: element v of lane l is output column 8*(v/4) + 4*(l/32) + v%4 of
 // activation row l%32.  Four consecutive v are four consecutive columns of one row, which lets
@@ -135,29 +152,30 @@ constexpr int kRing = 4;   // weight operands of this many k-steps are in flight
 // acc[i][j] += W[cols of block nb0+j][K] * A[rows 32i..32i+32)[K]^T, KS a multiple of kRing.
 // The weight operands sit in a ring of kRing register buffers; a buffer is refilled for k-step
 // ks + kRing right after the MFMAs of k-step ks have been issued, so no load is waited for in the
-// step that issues it and no register is copied.  wbase is wave-uniform; lane_off = 16 * lane.
+// step that issues it and no register is copied.
+// fb holds k-steps 0 .. kRing-1 of this layer on entry.  The last kRing refills of the loop fetch the
+// first k-steps of the NEXT GEMM (operand array nws, nKS k-steps per column block, nnb_total column
+// blocks), so that one starts without waiting for memory: its operands arrive during the epilogue
+// in between.
 template <int MI>
 __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const uint4* __restrict__ ws, uint32_t KS,
-                                          uint32_t nb0, uint32_t nb_total, uint32_t lane, f32x16 (&acc)[MI][kNI])
+                                          uint32_t nb0, uint32_t nb_total, uint32_t lane, f32x16 (&acc)[MI][kNI],
+                                          uint4 (&fb)[kRing][kNI], const uint4* __restrict__ nws, uint32_t nKS,
+                                          uint32_t nnb_total)
 {
-    if (nb0 >= nb_total) return; // this wave has no columns in this layer
+    if (nb0 >= nb_total) { // this wave has no columns in this layer
+        ring_fill(fb, nws, nKS, nb0, nnb_total, lane);
+        return;
+    }
     const uint16_t* arow = A + (lane & 31u) * lda + 8u * (lane >> 5);
-    // a column block past the end repeats the last one; its results are never stored
-    const uint4* wl[kNI];
+    // a column block past the end repeats the last one; its results are never used
+    const uint4 *wl[kNI], *nwl[kNI];
 #pragma unroll
     for (int j = 0; j < kNI; ++j) {
         const uint32_t nb = nb0 + j < nb_total ? nb0 + j : nb_total - 1u;
         wl[j] = ws + (size_t)nb * KS * 64u;
-    }
-    uint4 fb[kRing][kNI];
-#pragma unroll
-    for (int s = 0; s < kRing; ++s) {
-#pragma unroll
-        for (int j = 0; j < kNI; ++j) fb[s][j] = wl[j][s * 64 + lane];
-        // issue the ring's first loads in ring order: the counter wait in front of an MFMA is
-        // placed for the worst order on any path into the loop, and a prefill issued out of
-        // order makes every k-step wait for the newest load instead of the oldest
-        __builtin_amdgcn_sched_barrier(0);
+        const uint32_t nnb = nb0 + j < nnb_total ? nb0 + j : nnb_total - 1u;
+        nwl[j] = nws + (size_t)nnb * nKS * 64u;
     }
     // the activation operands are double-buffered too: those of k-step ks+1 are read from shared
     // memory before the MFMAs of k-step ks are issued (H has 8 columns of padding, so the read
@@ -166,6 +184,13 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
 #pragma unroll
     for (int i = 0; i < MI; ++i) fa[0][i] = *reinterpret_cast<const uint4*>(arow + (size_t)i * 32u * lda);
     for (uint32_t k0 = 0; k0 < KS; k0 += kRing) {
+        // where this round's refills come from: further down this layer, or the start of the next
+        // GEMM (a select between wave-uniform pointers: no branch around the loads, which would
+        // make the counter waits drain the ring)
+        const bool more = k0 + kRing < KS;
+        const uint4* src[kNI];
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) src[j] = more ? wl[j] + (size_t)(k0 + kRing) * 64u : nwl[j];
 #pragma unroll
         for (int s = 0; s < kRing; ++s) {
             const uint32_t kn = k0 + s + 1u < KS ? k0 + s + 1u : k0 + s;
@@ -180,10 +205,9 @@ __device__ __forceinline__ void wave_gemm(const uint16_t* A, uint32_t lda, const
                 for (int i = 0; i < MI; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, as_frag(fa[s & 1][i]), acc[i][j], 0, 0, 0);
             }
-            // refill for k-step k0 + s + kRing; past the end this reads the next block (or the
-            // padding behind the last one) and is never used
+            // refill for k-step k0 + s + kRing (or k-step s of the next GEMM)
 #pragma unroll
-            for (int j = 0; j < kNI; ++j) fb[s][j] = wl[j][(k0 + kRing + s) * 64u + lane];
+            for (int j = 0; j < kNI; ++j) fb[s][j] = src[j][s * 64u + lane];
             // keep the refill here: left alone, the scheduler sinks it to just before its use
             // (to save registers) and every k-step then waits a full memory latency
             __builtin_amdgcn_sched_barrier(0);
@@ -332,6 +356,9 @@ __device__ __forceinline__ void run_tiles(const FusedArgs& a, const FusedSmem& m
             }
         }
     }
+    // weight operands of layer 1's first k-steps; from here on every GEMM leaves the ring filled for the next one
+    uint4 fb[kRing][kNI];
+    ring_fill(fb, a.w1s, k1p / 16u, wave * kNI, nb1, threadIdx.x & 63u);
     uint32_t cur = 0;
     for (uint32_t ti = 0; ti < n_tiles; ++ti) {
         const uint32_t row0 = row_begin + ti * TM;
@@ -367,14 +394,15 @@ __device__ __forceinline__ void run_tiles(const FusedArgs& a, const FusedSmem& m
         f32x16 acc[MI][kNI];
         // layer 1
         bias_acc<MI>(acc, m.s_b1, n0, lane);
-        wave_gemm<MI>(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc);
+        wave_gemm<MI>(H, ldx, a.w1s, k1p / 16u, wave * kNI, nb1, lane, acc, fb, a.w2s, k2p / 16u, nb2);
         __syncthreads(); // every wave has read the input tile; H may be overwritten
         if (tid < TM) flow_next[tid] = nf;
         store_hidden<MI>(H, acc, n0, k2p, nb1, lane);
         __syncthreads();
         // layer 2
         bias_acc<MI>(acc, m.s_b2, n0, lane);
-        wave_gemm<MI>(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc);
+        // (the ring goes on to layer 1 of the next tile; after the last tile the fetch is not used)
+        wave_gemm<MI>(H, LDH, a.w2s, k2p / 16u, wave * kNI, nb2, lane, acc, fb, a.w1s, k1p / 16u, nb1);
         __syncthreads();
         store_hidden<MI>(H, acc, n0, k3p, nb2, lane);
         // layer 3: wave = (row block rb, half kh of K); waves beyond MI x 2 only keep the barriers.  The hidden
