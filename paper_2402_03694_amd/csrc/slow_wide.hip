@@ -31,7 +31,6 @@ constexpr int WSLAB = 64;         // K values per slab
 constexpr int WLDS = WSLAB + 8;   // slab row stride (elements)
 constexpr int WLDO = WBN + 8;     // output tile row stride (elements)
 constexpr int WRING = 4;          // = k-steps per slab
-constexpr uint32_t kDies = 8;     // accelerator dies; block b runs on die b mod 8
 constexpr size_t kWideLds = (size_t)WBM * WLDO * 2 + WBM * 4; // output tile (covers both slabs) + flow ids
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -46,7 +45,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 }
 
 template <int AMODE>
-__global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const uint4* __restrict__ ws, uint32_t n_rb, uint32_t n_cb)
+__global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const uint4* __restrict__ ws)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t* slab = reinterpret_cast<uint16_t*>(smem);                          // [2][128][WLDS]
@@ -54,17 +53,11 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
     uint32_t* s_flow = reinterpret_cast<uint32_t*>(smem + (size_t)WBM * WLDO * 2); // [128]
     uint32_t total = *a.esc_count;
     total = total < a.esc_cap ? total : a.esc_cap;
-    // Block number -> tile.  Consecutive block numbers go to different dies (8 of them, each with
-    // its own L2), so the column blocks that share a row block are dealt to one die, next to each
-    // other in its sequence: the row block's A operand is then fetched from memory once, not once
-    // per column block.
-    const uint32_t seq = blockIdx.x / kDies, die = blockIdx.x % kDies;
-    const uint32_t rb = (seq / n_cb) * kDies + die, cb = seq % n_cb;
-    const uint32_t row0 = a.row_begin + rb * WBM; // first escalated row of this block
-    if (rb >= n_rb || row0 >= total) return; // padding of the last round, or past the device-side count
+    const uint32_t row0 = a.row_begin + blockIdx.x * WBM; // first escalated row of this block
+    if (row0 >= total) return;
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t col0 = cb * WBN;
+    const uint32_t col0 = blockIdx.y * WBN;
     const uint32_t nb_total = (a.N + 31u) / 32u;
     const uint32_t KS = (a.K + WSLAB - 1) / WSLAB * WRING; // k-steps, padded to whole slabs
     const uint32_t n_slabs = KS / WRING;
@@ -83,7 +76,7 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
     uint4 ra[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
-        ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, rb * WBM + cr[u], AMODE != A_BF16 ? s_flow[cr[u]] : 0u, ck);
+        ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u], AMODE != A_BF16 ? s_flow[cr[u]] : 0u, ck);
 #pragma unroll
     for (int u = 0; u < 2; ++u) *reinterpret_cast<uint4*>(slab + cr[u] * WLDS + ck) = ra[u];
 
@@ -126,7 +119,7 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
         if (more) {
 #pragma unroll
             for (int u = 0; u < 2; ++u)
-                ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, rb * WBM + cr[u],
+                ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u],
                                             AMODE != A_BF16 ? s_flow[cr[u]] : 0u, (sl + 1) * WSLAB + ck);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -182,7 +175,7 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
         const uint32_t r = c / (WBN / 8), k = (c % (WBN / 8)) * 8u;
         if (row0 + r < total && col0 + k < a.ldh) {
             const uint4 v = *reinterpret_cast<const uint4*>(otile + r * WLDO + k);
-            uint16_t* dst = a.h_out + (size_t)(rb * WBM + r) * a.ldh + col0 + k;
+            uint16_t* dst = a.h_out + (size_t)(blockIdx.x * WBM + r) * a.ldh + col0 + k;
             if (col0 + k + 8u <= a.ldh && (a.ldh & 7u) == 0) {
                 *reinterpret_cast<uint4*>(dst) = v;
             } else {
@@ -197,9 +190,8 @@ template <int AMODE>
 int launch_wide(sf_ctx* ctx, const LayerArgs& a, const void* w_ordered, uint32_t rows_cap)
 {
     SF_ALLOW_LDS(ctx, sf::kLdsWide + AMODE, mlp_wide_layer<AMODE>);
-    const uint32_t n_rb = (rows_cap + WBM - 1) / WBM, n_cb = (a.ldh + WBN - 1) / WBN;
-    const uint32_t grid = (n_rb + kDies - 1) / kDies * kDies * n_cb; // row blocks rounded up to whole rounds of the dies
-    mlp_wide_layer<AMODE><<<grid, WWAVES * 64, kWideLds, ctx->stream>>>(a, (const uint4*)w_ordered, n_rb, n_cb);
+    dim3 grid((rows_cap + WBM - 1) / WBM, (a.ldh + WBN - 1) / WBN);
+    mlp_wide_layer<AMODE><<<grid, WWAVES * 64, kWideLds, ctx->stream>>>(a, (const uint4*)w_ordered);
     SF_LAUNCH_CHECK(ctx, "mlp_wide_layer");
     return SF_OK;
 }
