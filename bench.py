@@ -550,6 +550,11 @@ def kernel_report(tt, cfg_id, n, n_pkts, n_esc, avg, probe):
     dominant = names[int(np.argmax(avg))]
     roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
     roof["kernel"] = dominant
+    # a tree walk is bound by its gathers, not by HBM: its rate against the all-from-shared-memory gather bound
+    # (from the probe of this same run) goes beside the HBM fraction
+    for k in ("visits_per_s", "gather_bound_visits_per_s", "gather_frac"):
+        if k in kernels[dominant]:
+            roof[k] = kernels[dominant][k]
     return roof, kernels
 
 
