@@ -4,8 +4,9 @@
 // One lane owns one flow and keeps its packets in registers; the statistics of a window are
 // computed by the shared device code in featurize_core.h (ordered sums, one sorting network and
 // one merge stage per quantity for the order statistics), so the result does not depend on how
-// flows are spread over lanes.  A block is one wave: its 64 feature rows are staged in shared
-// memory per window and written out as full 128-byte runs.
+// flows are spread over lanes.  A window of more than 32 packets is worked on by the whole wave
+// (a sort across the lanes; see below).  A block is one wave: its 64 feature rows are staged in
+// shared memory per window and written out as full 128-byte runs.
 #include "common.h"
 #include "featurize_core.h"
 
@@ -80,10 +81,187 @@ __device__ __forceinline__ void decode_wide(const RawPackets<KMAX>& r, float (&s
     }
 }
 
+// ---- windows deeper than 32 packets ---------------------------------------------------------------------
+// A lane keeps at most 32 packets in registers (a 64-element network per lane needs more registers than a
+// lane has, and its straight-line code no longer fits the instruction cache).  A flow whose window holds
+// more than 32 packets is worked on by the whole wave instead, in two steps:
+//   order statistics  lane p holds packet p; six arrays (quantity x group, padded with the largest key) are
+//                     sorted at once by a bitonic network across the lanes, and the flow's values are parked
+//                     in shared memory;
+//   ordered sums      for up to kSlots parked flows at once: six lanes per flow, each walking one
+//                     (quantity, group) chain packet by packet.
+// The arithmetic per value is the one of sffeat::window_stats.
+
+constexpr uint32_t kSlots = 10;                 // flows whose chains run side by side (6 lanes each)
+constexpr uint32_t kSlotWords = 2 * kWave + 8;  // parked per flow: 64 sizes, 64 times, then lane, packets, direction mask
+
+__device__ __forceinline__ uint32_t lane_value(uint32_t x, int p) { return (uint32_t)__builtin_amdgcn_readlane((int)x, p); }
+
+// the value of lane (lane ^ J): within four lanes and across half a row of 16 by a data-parallel move,
+// otherwise through the shared-memory crossbar
+template <uint32_t J>
+__device__ __forceinline__ uint32_t from_lane_xor(uint32_t v)
+{
+    if (J == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+    if (J == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+    if (J == 8) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false); // row_ror:8
+    return (uint32_t)__shfl_xor((int)v, (int)J, kWave);
+}
+
+template <uint32_t K, uint32_t J>
+__device__ __forceinline__ void sort6_step(uint32_t (&key)[6], uint32_t lane)
+{
+    const bool up = (lane & K) == 0; // (K = 64: every lane)
+    const bool lower = (lane & J) == 0;
+    uint32_t other[6];
+#pragma unroll
+    for (int c = 0; c < 6; ++c) other[c] = from_lane_xor<J>(key[c]);
+#pragma unroll
+    for (int c = 0; c < 6; ++c) {
+        const uint32_t lo = key[c] < other[c] ? key[c] : other[c], hi = key[c] < other[c] ? other[c] : key[c];
+        key[c] = lower == up ? lo : hi;
+    }
+}
+template <uint32_t K, uint32_t J>
+__device__ __forceinline__ void sort6_merge(uint32_t (&key)[6], uint32_t lane)
+{
+    sort6_step<K, J>(key, lane);
+    if constexpr (J > 1) sort6_merge<K, J / 2>(key, lane);
+}
+// Six independent arrays of one key per lane, each sorted ascending by lane; the six exchanges of a step are
+// issued together so that their latencies overlap.
+__device__ __forceinline__ void wave_sort6(uint32_t (&key)[6], uint32_t lane)
+{
+    sort6_merge<2, 1>(key, lane);
+    sort6_merge<4, 2>(key, lane);
+    sort6_merge<8, 4>(key, lane);
+    sort6_merge<16, 8>(key, lane);
+    sort6_merge<32, 16>(key, lane);
+    sort6_merge<64, 32>(key, lane);
+}
+
+// lane p's packet of a window of m packets that start at packet o (zeros past the window), as loaded: nothing
+// is computed from it here, so that the request can be issued a whole flow ahead of its use
+struct LanePacket {
+    uint32_t sz, d;
+    float tm;
+};
+__device__ __forceinline__ LanePacket long_flow_load(const FeatArgs& a, uint32_t o, int m, uint32_t lane)
+{
+    LanePacket r = {0u, 0u, 0.f};
+    if ((int)lane < m) {
+        r.sz = a.size[o + lane];
+        r.tm = a.iat[o + lane];
+        r.d = a.dir[o + lane];
+    }
+    return r;
+}
+
+// Sort keys of a window of m packets (32 < m <= 64), lane p holding packet p: array c = 3 * quantity + group,
+// padded with the largest key; c0 / c1: packets of direction 0 / 1.  The values are parked in slot[] for the
+// chains.  Every lane of the wave takes part, m and src_lane are the same in all of them.
+__device__ __forceinline__ void long_flow_keys(const LanePacket& pk, int m, uint32_t src_lane, uint32_t lane, uint32_t* slot,
+                                               uint32_t (&key)[6], int& c0, int& c1)
+{
+    const bool valid = (int)lane < m;
+    const float sz = (float)pk.sz, tm = pk.tm;
+    const uint32_t d = pk.d & 1u;
+    const uint64_t vmask = __ballot(valid), m1 = __ballot(valid && d != 0), m0 = vmask & ~m1;
+    c1 = __popcll(m1);
+    c0 = m - c1;
+    slot[lane] = __float_as_uint(sz);
+    slot[kWave + lane] = __float_as_uint(tm);
+    if (lane == 0u) {
+        slot[2 * kWave + 0] = src_lane;
+        slot[2 * kWave + 1] = (uint32_t)m;
+        slot[2 * kWave + 2] = (uint32_t)m1;
+        slot[2 * kWave + 3] = (uint32_t)(m1 >> 32);
+    }
+#pragma unroll
+    for (uint32_t c = 0; c < 6u; ++c) {
+        const uint32_t g = c % 3u, q = c / 3u;
+        const uint64_t gm = g == 0 ? m0 : (g == 1 ? m1 : vmask);
+        const bool in = (gm >> lane) & 1ull;
+        key[c] = in ? (q ? sffeat::order_key(tm) : (uint32_t)sz) : 0xFFFFFFFFu;
+    }
+}
+
+// Order statistics from the keys -> dst[10g + 5q + 2..4]
+__device__ __forceinline__ void long_flow_order_stats(uint32_t (&key)[6], int m, int c0, int c1, uint32_t lane, float* dst)
+{
+    wave_sort6(key, lane);
+#pragma unroll
+    for (uint32_t c = 0; c < 6u; ++c) {
+        const uint32_t g = c % 3u, q = c / 3u;
+        const int cg = g == 0 ? c0 : (g == 1 ? c1 : m);
+        const int last = cg > 0 ? cg - 1 : 0;
+        const uint32_t k_mn = lane_value(key[c], 0), k_mx = lane_value(key[c], last);
+        const uint32_t k_lo = lane_value(key[c], last >> 1), k_hi = lane_value(key[c], cg >> 1);
+        const float mn = q ? sffeat::from_key(k_mn) : (float)k_mn, mx = q ? sffeat::from_key(k_mx) : (float)k_mx;
+        const float lo = q ? sffeat::from_key(k_lo) : (float)k_lo, hi = q ? sffeat::from_key(k_hi) : (float)k_hi;
+        const float two = lo + hi;
+        if (lane == 0u) {
+            dst[10u * g + 5u * q + 2u] = cg == 0 ? 0.f : mn;
+            dst[10u * g + 5u * q + 3u] = cg == 0 ? 0.f : mx;
+            dst[10u * g + 5u * q + 4u] = cg == 0 ? 0.f : ((cg & 1) ? hi : two * 0.5f);
+        }
+    }
+}
+
+// Means, standard deviations, byte and packet counts of the n_slots parked flows -> their staged rows
+// (tile + lane_of_flow * kRow).  Lane 6k + c carries chain c (quantity c / 3, group c % 3) of slot k.
+__device__ __forceinline__ void long_flow_chains(const uint32_t* park, uint32_t n_slots, uint32_t lane, float* tile)
+{
+    const uint32_t k = lane / 6u, c = lane - 6u * k;
+    if (k >= n_slots) return;
+    const uint32_t g = c % 3u, q = c / 3u;
+    const uint32_t* slot = park + k * kSlotWords;
+    const uint32_t src_lane = slot[2 * kWave + 0];
+    const int m = (int)slot[2 * kWave + 1];
+    const uint64_t m1 = (uint64_t)slot[2 * kWave + 2] | ((uint64_t)slot[2 * kWave + 3] << 32);
+    const uint64_t valid = m >= 64 ? ~0ull : ((1ull << m) - 1ull);
+    const uint64_t in_mask = g == 0 ? valid & ~m1 : (g == 1 ? m1 : valid);
+    const int cg = __popcll(in_mask);
+    const float ng = (float)(cg > 0 ? cg : 1);
+    const float* x = reinterpret_cast<const float*>(slot) + q * kWave;
+    float sum = 0.f;
+    for (int p = 0; p < kWave; p += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(x + p);
+        const uint32_t in4 = (uint32_t)(in_mask >> p) & 15u;
+        sum = sum + ((in4 & 1u) ? v.x : 0.f);
+        sum = sum + ((in4 & 2u) ? v.y : 0.f);
+        sum = sum + ((in4 & 4u) ? v.z : 0.f);
+        sum = sum + ((in4 & 8u) ? v.w : 0.f);
+    }
+    const float mean = sum / ng;
+    float acc = 0.f;
+    for (int p = 0; p < kWave; p += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(x + p);
+        const uint32_t in4 = (uint32_t)(in_mask >> p) & 15u;
+        const float d0 = v.x - mean, d1 = v.y - mean, d2 = v.z - mean, d3 = v.w - mean;
+        const float e0 = d0 * d0, e1 = d1 * d1, e2 = d2 * d2, e3 = d3 * d3;
+        acc = acc + ((in4 & 1u) ? e0 : 0.f);
+        acc = acc + ((in4 & 2u) ? e1 : 0.f);
+        acc = acc + ((in4 & 4u) ? e2 : 0.f);
+        acc = acc + ((in4 & 8u) ? e3 : 0.f);
+    }
+    const float var = acc / ng;
+    float* dst = tile + src_lane * kRow;
+    dst[10u * g + 5u * q + 0u] = cg == 0 ? 0.f : mean;
+    dst[10u * g + 5u * q + 1u] = cg == 0 ? 0.f : sqrtf(var);
+    if (c == 2u) { // sizes, all packets
+        dst[30] = sum;
+        dst[31] = (float)m;
+    }
+}
+
+// KMAX: packets a lane keeps in registers.  LONG: windows may be deeper than that (up to 64 packets); flows
+// with more than KMAX packets in a window then go through long_window_stats.
 // (second launch bound: waves per SIMD the register allocation aims for: three up to 16 packets per flow)
-template <int KMAX>
+template <int KMAX, bool LONG>
 __global__ __launch_bounds__(kWave, (KMAX <= 16 ? 3 : 1)) void featurize_wave(FeatArgs a)
 {
+    static_assert(!LONG || KMAX == 32, "the whole-wave path takes over above 32 packets");
     __shared__ uint32_t sort_col[KMAX * kWave]; // [rank][lane]
     __shared__ float tile[kWave * kRow];        // [lane][33]
     const uint32_t lane = threadIdx.x;
@@ -93,7 +271,8 @@ __global__ __launch_bounds__(kWave, (KMAX <= 16 ? 3 : 1)) void featurize_wave(Fe
     uint32_t o = 0, n = 0;
     if (live) flow_range(a, i, o, n);
     const uint32_t dmax = a.depth[a.n_windows - 1];
-    const int avail = (int)(n < dmax ? n : dmax);
+    const int avail_w = (int)(n < dmax ? n : dmax);              // packets of the deepest window
+    const int avail = avail_w < KMAX ? avail_w : KMAX;           // of which the lane holds in registers
     float s[KMAX], t[KMAX];
     uint64_t dmask = 0;
     if (avail == KMAX && (o & 7u) == 0 && a.wide_ok) {
@@ -125,16 +304,47 @@ __global__ __launch_bounds__(kWave, (KMAX <= 16 ? 3 : 1)) void featurize_wave(Fe
     rows = rows < (uint32_t)kWave ? rows : (uint32_t)kWave;
     for (uint32_t w = 0; w < a.n_windows; ++w) {
         const int dw = (int)a.depth[w];
-        const int m = avail < dw ? avail : dw;
+        const int m_w = avail_w < dw ? avail_w : dw;
+        const bool long_flow = LONG && m_w > KMAX;
+        const int m = long_flow ? 0 : m_w; // (the lane's own result for such a flow is overwritten below)
         // the smallest network that covers every lane's window (wave-uniform choice)
-        if (KMAX >= 64 && __any(m > 32))
-            sffeat::window_stats<(KMAX >= 64 ? 64 : KMAX), KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
-        else if (KMAX >= 32 && __any(m > 16))
+        if (KMAX >= 32 && __any(m > 16))
             sffeat::window_stats<(KMAX >= 32 ? 32 : KMAX), KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
         else if (KMAX >= 16 && __any(m > 8))
             sffeat::window_stats<(KMAX >= 16 ? 16 : KMAX), KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
         else
             sffeat::window_stats<8, KMAX>(s, t, dmask, m, signed_times, col, kWave, row, 1u);
+        if (LONG) {
+            // (the sort scratch of the lanes' own windows is free by now: the long flows' values are parked there)
+            static_assert(!LONG || kSlots * kSlotWords <= (uint32_t)KMAX * kWave, "parked flows fit the sort scratch");
+            uint64_t todo = __ballot(long_flow);
+            // the packets of the next long flow are requested while the current one is sorted
+            int l = todo ? __ffsll((unsigned long long)todo) - 1 : 0;
+            int m_l = todo ? (int)lane_value((uint32_t)m_w, l) : 0;
+            LanePacket cur = long_flow_load(a, lane_value(o, l), m_l, lane);
+            while (todo) {
+                uint32_t n_slots = 0;
+                while (todo && n_slots < kSlots) {
+                    todo &= todo - 1ull;
+                    const int l_next = todo ? __ffsll((unsigned long long)todo) - 1 : 0;
+                    const int m_next = todo ? (int)lane_value((uint32_t)m_w, l_next) : 0;
+                    uint32_t key[6];
+                    int c0, c1;
+                    long_flow_keys(cur, m_l, (uint32_t)l, lane, sort_col + n_slots * kSlotWords, key, c0, c1);
+                    // (requested only now, behind the wait for the current flow's packets, and pinned here: the
+                    // request then flies while the current flow is sorted)
+                    __builtin_amdgcn_sched_barrier(0);
+                    const LanePacket next = long_flow_load(a, lane_value(o, l_next), m_next, lane);
+                    __builtin_amdgcn_sched_barrier(0);
+                    long_flow_order_stats(key, m_l, c0, c1, lane, tile + l * kRow);
+                    ++n_slots;
+                    cur = next;
+                    l = l_next;
+                    m_l = m_next;
+                }
+                long_flow_chains(sort_col, n_slots, lane, tile);
+            }
+        }
         __syncthreads();
         if (a.store16) {
             // eight lanes write one staged row (32 consecutive floats = one 128-byte run) as 16-byte pieces:
@@ -229,13 +439,13 @@ extern "C" int sf_featurize(sf_ctx* ctx, const sf_packets* pk, const sf_feat_cfg
     const uint32_t dmax = cfg->depth[cfg->n_windows - 1];
     const uint32_t grid = (a.n_flows + kWave - 1) / kWave;
     if (dmax <= 8)
-        featurize_wave<8><<<grid, kWave, 0, ctx->stream>>>(a);
+        featurize_wave<8, false><<<grid, kWave, 0, ctx->stream>>>(a);
     else if (dmax <= 16)
-        featurize_wave<16><<<grid, kWave, 0, ctx->stream>>>(a);
+        featurize_wave<16, false><<<grid, kWave, 0, ctx->stream>>>(a);
     else if (dmax <= 32)
-        featurize_wave<32><<<grid, kWave, 0, ctx->stream>>>(a);
+        featurize_wave<32, false><<<grid, kWave, 0, ctx->stream>>>(a);
     else
-        featurize_wave<64><<<grid, kWave, 0, ctx->stream>>>(a);
+        featurize_wave<32, true><<<grid, kWave, 0, ctx->stream>>>(a);
     SF_LAUNCH_CHECK(ctx, "featurize");
     if (raw) {
         const uint64_t total = (uint64_t)a.n_flows * cfg->raw_pkts * ((cfg->raw_bits + 31) / 32);

@@ -111,6 +111,34 @@ def test_featurize_extreme_values_and_signed_times(cfg_id, n):
     _assert_feat_equal(got, want, pk)
 
 
+@pytest.mark.parametrize("depths,geom_p,pkts", [((8, 64), 0.02, None), ((33,), 0.03, None), ((40, 64), 0.03, None),
+                                                 ((16, 32, 33, 64), 0.05, None), ((8, 64), 0.1, 64), ((5, 48), 0.1, 33)])
+def test_featurize_windows_deeper_than_32(depths, geom_p, pkts):
+    """Windows of more than 32 packets: a flow that fills them is worked on by the whole wave (a sort across the
+    lanes), the others by their own lane.  Length mixes with many long flows (up to every lane of a wave), windows
+    of exactly 32 and 33 packets, fixed lengths 33 and 64; a block of ties, extreme values and one-direction flows;
+    negative times in every fourth wave."""
+    from dataclasses import replace
+    cfg = replace(synth.get_config(4), depths=depths, geom_p=geom_p, pkts_per_flow=pkts)
+    pk = synth.make_packets(cfg, n_flows=1500 + 7)
+    rng = np.random.default_rng(29)
+    lens = np.diff(pk.flow_off.astype(np.int64))
+    flow_of_pkt = np.repeat(np.arange(pk.n_flows), lens)
+    ties = (flow_of_pkt // 64) % 5 == 1
+    pk.pkt_size = np.where(ties, rng.choice(np.array([0, 60, 60, 1500, 65535], np.uint16), size=pk.n_pkts), pk.pkt_size)
+    iat = pk.pkt_iat.copy()
+    iat[ties] = rng.choice(np.array([0.0, 0.5, 0.5, 1e-38, 3.4028235e38], np.float32), size=int(ties.sum()))
+    neg = (flow_of_pkt // 64) % 4 == 2
+    iat[neg] = rng.choice(np.array([-2.5, -1e-3, 0.5, 7.0, -3.0e38], np.float32), size=int(neg.sum()))
+    pk.pkt_iat = iat
+    one_dir = (flow_of_pkt // 64) % 7 == 3
+    pk.pkt_dir = np.where(one_dir, (flow_of_pkt % 2).astype(np.uint8), pk.pkt_dir)
+    assert (lens > 32).sum() >= 100
+    want, _ = oracle.featurize(pk.flow_off, pk.pkt_size, pk.pkt_iat, pk.pkt_dir, cfg.depths, n_threads=8)
+    got, _ = _run(cfg, pk).featurize()
+    _assert_feat_equal(got, want, pk)
+
+
 def test_featurize_raw_bits():
     cfg = synth.get_config(3)
     pk = synth.make_packets(cfg, n_flows=300)
