@@ -43,21 +43,26 @@ __device__ __forceinline__ uint4 load_w_chunk(const LayerArgs& a, uint32_t n, ui
 }
 
 // The last layer of a wide model: logits = A * W3^T + b3 on bfloat16 activations (at most BN classes), then the
-// arg-max per row and the scatter of the label.  128 rows per block, four waves of 32 rows each.
+// arg-max per row and the scatter of the label.  128 rows per block, four waves of 32 rows each.  K is walked
+// in steps of 128; the operands of the next step are requested before the MFMAs of the current one, so that
+// a launch with few blocks (a small batch) does not wait a whole memory latency per step.
+constexpr int LBK = 128;      // K per step of the last layer
+constexpr int LLDT = LBK + 8; // shared-memory row stride (elements): 272 bytes, 16-byte reads of 8 consecutive rows on distinct banks
+
 template <int BN>
 __global__ __launch_bounds__(256) void mlp_last_layer(LayerArgs a)
 {
     constexpr int MI = 1, NI = BN / 32;   // a wave owns 32 rows x BN columns
     constexpr int WM = BM / 4;
-    constexpr int A_CHUNKS = BM * BK / 8 / 256; // 16-byte chunks per thread per step
-    constexpr int B_CHUNKS = (BN * BK / 8 + 255) / 256;
-    constexpr int SM_AB = (BM + BN) * LDT * 2;
+    constexpr int A_CHUNKS = BM * LBK / 8 / 256; // 16-byte chunks per thread per step
+    constexpr int B_CHUNKS = (BN * LBK / 8 + 255) / 256;
+    constexpr int SM_AB = (BM + BN) * LLDT * 2;
     constexpr int SM_EPI = BM * (BN + 1) * 4;
     constexpr int SM_BYTES = SM_AB > SM_EPI ? SM_AB : SM_EPI;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SM_BYTES];
     __shared__ uint32_t s_flow[BM];
     uint16_t* As = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Bs = As + BM * LDT;
+    uint16_t* Bs = As + BM * LLDT;
 
     uint32_t total = *a.esc_count;
     total = total < a.esc_cap ? total : a.esc_cap;
@@ -67,7 +72,6 @@ __global__ __launch_bounds__(256) void mlp_last_layer(LayerArgs a)
 
     if (tid < BM) // the index the row's label goes to
         s_flow[tid] = row0 + tid < total ? (a.scatter ? a.scatter[row0 + tid] : a.esc_idx[row0 + tid]) : 0u;
-    __syncthreads();
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -77,40 +81,45 @@ __global__ __launch_bounds__(256) void mlp_last_layer(LayerArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    for (uint32_t k0 = 0; k0 < a.K; k0 += BK) {
-        uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+    auto fetch = [&](uint32_t k0) {
 #pragma unroll
         for (int u = 0; u < A_CHUNKS; ++u) {
-            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
+            const uint32_t c = tid + 256 * u, r = c / (LBK / 8), kq = c % (LBK / 8);
             ra[u] = load_a_chunk<A_BF16>(a, row0 + r < total, blockIdx.x * BM + r, 0u, k0 + kq * 8);
         }
 #pragma unroll
         for (int u = 0; u < B_CHUNKS; ++u) {
-            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
+            const uint32_t c = tid + 256 * u, r = c / (LBK / 8), kq = c % (LBK / 8);
             rb[u] = (r < (uint32_t)BN) ? load_w_chunk(a, r, k0 + kq * 8) : make_uint4(0, 0, 0, 0);
         }
-        __syncthreads(); // previous step's fragment reads are done
+    };
+    fetch(0);
+    for (uint32_t k0 = 0; k0 < a.K; k0 += LBK) {
+        __syncthreads(); // previous step's fragment reads are done (first step: s_flow is in place)
 #pragma unroll
         for (int u = 0; u < A_CHUNKS; ++u) {
-            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
-            *reinterpret_cast<uint4*>(As + r * LDT + kq * 8) = ra[u];
+            const uint32_t c = tid + 256 * u, r = c / (LBK / 8), kq = c % (LBK / 8);
+            *reinterpret_cast<uint4*>(As + r * LLDT + kq * 8) = ra[u];
         }
 #pragma unroll
         for (int u = 0; u < B_CHUNKS; ++u) {
-            const uint32_t c = tid + 256 * u, r = c / (BK / 8), kq = c % (BK / 8);
-            if (r < (uint32_t)BN) *reinterpret_cast<uint4*>(Bs + r * LDT + kq * 8) = rb[u];
+            const uint32_t c = tid + 256 * u, r = c / (LBK / 8), kq = c % (LBK / 8);
+            if (r < (uint32_t)BN) *reinterpret_cast<uint4*>(Bs + r * LLDT + kq * 8) = rb[u];
         }
         __syncthreads();
+        if (k0 + LBK < a.K) fetch(k0 + LBK); // chunks past K read as zeros
+        __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the MFMAs
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
+        for (int ks = 0; ks < LBK / 16; ++ks) {
             bf16x8 fa[MI], fb[NI];
             const uint32_t kofs = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
             for (int i = 0; i < MI; ++i)
-                fa[i] = as_bf16x8(*reinterpret_cast<const uint4*>(As + (wm * WM + i * 32 + (lane & 31)) * LDT + kofs));
+                fa[i] = as_bf16x8(*reinterpret_cast<const uint4*>(As + (wm * WM + i * 32 + (lane & 31)) * LLDT + kofs));
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-                fb[j] = as_bf16x8(*reinterpret_cast<const uint4*>(Bs + (j * 32 + (lane & 31)) * LDT + kofs));
+                fb[j] = as_bf16x8(*reinterpret_cast<const uint4*>(Bs + (j * 32 + (lane & 31)) * LLDT + kofs));
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
