@@ -14,6 +14,8 @@
 // shared memory; nothing in the voting form rounds.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace sfforest {
@@ -66,7 +68,10 @@ struct FastArgs {
     uint16_t vmin[SF_MAX_CLASSES];
 };
 
-constexpr int kIlp = 8; // trees walked at once per lane (measured: 4 and 16 are slower)
+// Trees walked at once per lane: groups of kIlp, and a last group of kIlpTail when at most that many trees are
+// left (so that 100 trees take ten full groups and 125 twelve and a half, not thirteen of eight with four idle
+// slots; measured on 100 trees of depth 12: 8 at a time 0.565 ms, 10 at a time 0.532, 12 0.565, 20 0.553).
+constexpr int kIlp = 10, kIlpTail = 5;
 
 
 // Shared memory of a block behind the feature tile xT ([n_features][FPB] floats, FPB = BS / S flows):
@@ -169,7 +174,9 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
     // lane group g walks trees g, g+S, ...; every group runs the same number of rounds so that
     // the loop stays wave-uniform; a slot past the last tree repeats it and does not vote
     const uint32_t per_grp = (T + S - 1u) / S;
-    for (uint32_t q0 = 0; q0 < per_grp; q0 += kIlp) {
+    // one group: ILP trees from position q0 of the lane group's list
+    auto walk_group = [&](auto ilp_tag, uint32_t q0) {
+        constexpr int kIlp = decltype(ilp_tag)::value;
         uint32_t o[kIlp], tt[kIlp];
         bool tv[kIlp];
 #pragma unroll
@@ -226,7 +233,7 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
                     if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + tt[u]] = (uint16_t)leaf[u];
                 }
             }
-            continue;
+            return;
         }
         uint32_t lab[kIlp];
 #pragma unroll
@@ -240,6 +247,14 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
                 if (WANT_LEAF && live) a.leaf_idx[(size_t)i * T + tt[u]] = (uint16_t)leaf[u];
             }
         }
+    };
+    {
+        const uint32_t rem = per_grp % (uint32_t)kIlp;
+        const bool short_tail = rem != 0 && rem <= (uint32_t)kIlpTail;
+        const uint32_t full_end = short_tail ? per_grp - rem : per_grp; // (a longer tail runs as a full group with idle slots)
+        uint32_t q0 = 0;
+        for (; q0 < full_end; q0 += kIlp) walk_group(std::integral_constant<int, kIlp>{}, q0);
+        if (short_tail) walk_group(std::integral_constant<int, kIlpTail>{}, q0);
     }
 #undef SF_PAIR_STEP
 #undef SF_FEAT_0
