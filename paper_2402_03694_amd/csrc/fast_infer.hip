@@ -89,7 +89,7 @@ __global__ __launch_bounds__(BS) void forest_votes(FastArgs a)
             for (uint32_t f = grp; f < F; f += S) xT[f * FPB + slot] = x[f];
         }
     }
-    forest_walk<BS, S, WANT_LEAF, GBDT, false>(a, xT, i, row, live);
+    forest_walk<BS, S, WANT_LEAF, GBDT, false, (S > 1 || !GBDT)>(a, xT, i, row, live);
 }
 
 template <int BS, int S, bool GBDT>

@@ -87,7 +87,7 @@ constexpr int kIlp = 10, kIlpTail = 5;
 // live: false for lanes past the end (they walk a valid tile column and write nothing).
 // The caller has filled xT (no barrier needed before the call: this function synchronises the block
 // before the first read of the tile).
-template <int BS, int S, bool WANT_LEAF, bool GBDT, bool KEEP_ROWS>
+template <int BS, int S, bool WANT_LEAF, bool GBDT, bool KEEP_ROWS, bool EAGER = (S > 1)>
 __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32_t i, uint32_t row, bool live)
 {
     static_assert(!GBDT || S == 1, "margins are summed in tree order by one lane");
@@ -143,19 +143,20 @@ __device__ __forceinline__ void forest_walk(const FastArgs& a, float* xT, uint32
 #define SF_FEAT_0(FW) (kRot0 == 0u ? *(LdsFloat*)(uintptr_t)(((FW) & kFieldMask) | xl) : SF_FEAT_ROT(FW, kRot0))
 
     // two visits from one record; o is the byte offset of the record inside its tree.
-    // One lane per flow (S = 1, eight or more waves per compute unit): the child's feature is fetched
-    // after the parent's test (two shared-memory reads per record, the second dependent on the first):
-    // the shared-memory pipe is the scarcer resource there and the resident waves cover the latency.
-    // The record offset moves on as 4 * o + 16 * (1 + 2 * right0 + right1) = ((o + sh) << 2) - 16 + 16 * right1
-    // with sh = 8 or 16, the rotation that selects the child's feature field.
-    // Lanes sharing a flow (S = 2: forests whose shared-memory needs leave few waves resident): all
-    // three features up front (three independent reads), which is faster when latency binds.
+    // EAGER = false: the child's feature is fetched after the parent's test (two shared-memory reads per
+    // record, the second dependent on the first).  The record offset moves on as
+    // 4 * o + 16 * (1 + 2 * right0 + right1) = ((o + sh) << 2) - 16 + 16 * right1 with sh = 8 or 16, the rotation
+    // that selects the child's feature field.
+    // EAGER = true: all three features up front (three independent reads), which is faster when latency
+    // binds.  Which one wins is measured per kernel: lanes sharing a flow (few waves resident) and the
+    // stand-alone vote kernel run eager (workload 2: 0.564 -> 0.543 ms), the fused feature + forest kernel
+    // and the boosted form do not (0.531 against 0.570 ms, 0.72 against 0.78 ms).
 #define SF_PAIR_STEP(REC, O)                                                                              \
     do {                                                                                                  \
         const uint32_t fw = (REC).w;                                                                      \
         const float x0 = SF_FEAT_0(fw);                                                                   \
         const bool r0 = !(x0 <= __uint_as_float((REC).x));                                                \
-        if (S == 1) {                                                                                     \
+        if (!EAGER) {                                                                                     \
             const uint32_t sh = r0 ? 16u : 8u;                                                            \
             const float tc = __uint_as_float(r0 ? (REC).z : (REC).y);                                     \
             const float xc = SF_FEAT_ROT(fw, sh + kRot0);                                                 \
