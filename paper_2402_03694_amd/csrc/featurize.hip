@@ -257,9 +257,13 @@ __device__ __forceinline__ void long_flow_chains(const uint32_t* park, uint32_t 
 
 // KMAX: packets a lane keeps in registers.  LONG: windows may be deeper than that (up to 64 packets); flows
 // with more than KMAX packets in a window then go through long_window_stats.
-// (second launch bound: waves per SIMD the register allocation aims for: three up to 16 packets per flow)
+// (second launch bound: waves per SIMD the register allocation aims for.  Three up to 16 packets per flow.
+// Two with 32 packets in registers: the allocation then spills 28 registers per lane, and two waves that
+// cover each other's memory latency still win: 1.75 -> 1.37 ms on 4,194,304 flows of 32 packets; three waves
+// spill 160 registers and lose, 2.9 ms.  One where long flows go through the whole-wave path: that kernel's
+// time is a single wave's latency, which spills only lengthen.)
 template <int KMAX, bool LONG>
-__global__ __launch_bounds__(kWave, (KMAX <= 16 ? 3 : 1)) void featurize_wave(FeatArgs a)
+__global__ __launch_bounds__(kWave, (KMAX <= 16 ? 3 : (LONG ? 1 : 2))) void featurize_wave(FeatArgs a)
 {
     static_assert(!LONG || KMAX == 32, "the whole-wave path takes over above 32 packets");
     __shared__ uint32_t sort_col[KMAX * kWave]; // [rank][lane]
