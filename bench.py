@@ -522,6 +522,9 @@ def kernel_report(tt, cfg_id, n, n_pkts, n_esc, avg, probe):
         dominant = ["sf_featurize_fast_infer", "sf_featurize_fast_infer", "sf_route", "sf_slow_infer"][int(np.argmax(avg))]
         roof = {k: kernels[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
         roof["kernel"] = dominant
+        for k in ("visits_per_s", "gather_bound_visits_per_s", "gather_frac"):   # see below
+            if k in kernels[dominant]:
+                roof[k] = kernels[dominant][k]
         return roof, kernels
     flops = mlp_flops(cfg, n_esc)
     visits = float(n) * cfg.n_trees * cfg.tree_depth
