@@ -704,7 +704,7 @@ def main():
                          "workload, universal elsewhere")
     ap.add_argument("--calls", choices=["auto", "fused", "separate"], default="auto",
                     help="steps 1-3 as one kernel (sf_featurize_fast_infer) or as sf_featurize + sf_fast_infer; auto = fused "
-                         "for the headline workload (whose shape the fused kernel covers), with the separate calls timed "
+                         "for workloads 2 and 3 (whose shapes the fused kernel covers), for workload 2 with the separate calls timed "
                          "beside it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
@@ -748,7 +748,7 @@ def main():
     n = args.flows or cfg.n_flows
     tt = TwoTier(cfg, n, dev)
     vmin, how, _ = tt.calibrate(args)
-    want_fused = args.calls == "fused" or (args.calls == "auto" and args.config == 2)
+    want_fused = args.calls == "fused" or (args.calls == "auto" and args.config in (2, 3))
     if want_fused:
         # the fused kernel leaves the rows of the flows that stay with the fast model untouched: check that it ran
         tt.fused = True

@@ -121,7 +121,16 @@ def test_fused_header_bit_slow_model_without_a_feature_matrix():
     assert _check(cfg, pk, forest, mlp, 14, fused=True, use_feat=False) > 100
 
 
-@pytest.mark.parametrize("cfg_id,n,vmin", [(3, 1500 + 5, 14), (4, 3000 + 61, 19), (5, 1200 + 3, 25)])
+def test_fused_where_the_separate_forest_would_share_flows_between_lanes():
+    """Workload 3 as it stands (depth 10: the stand-alone forest kernel runs two lanes per flow): the fused kernel
+    runs one lane per flow and, the slow model reading header bits, writes no feature row."""
+    cfg = synth.get_config(3)
+    pk = synth.make_packets(cfg, n_flows=1500 + 5)
+    forest, mlp = _models(cfg, pk)
+    assert _check(cfg, pk, forest, mlp, 14, fused=True, use_feat=False) > 100
+
+
+@pytest.mark.parametrize("cfg_id,n,vmin", [(4, 3000 + 61, 19), (5, 1200 + 3, 25)])
 def test_shapes_that_run_the_separate_kernels(cfg_id, n, vmin):
     cfg = synth.get_config(cfg_id)
     pk = synth.make_packets(cfg, n_flows=n)
