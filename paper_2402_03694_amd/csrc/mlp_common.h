@@ -58,6 +58,49 @@ static __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
 
 static __device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
 
+// the packets of a flow for the raw-bit input: first packet and count, clamped into the packet arrays
+static __device__ __forceinline__ void raw_flow_range(const LayerArgs& a, uint32_t flow, uint32_t& b0, uint32_t& n)
+{
+    uint32_t e0 = a.off[flow + 1];
+    b0 = a.off[flow];
+    b0 = b0 < a.n_pkts ? b0 : a.n_pkts;
+    e0 = e0 < a.n_pkts ? e0 : a.n_pkts;
+    n = e0 > b0 ? e0 - b0 : 0;
+}
+
+// 8 consecutive raw-bit features [k, k+8) of a flow whose packets start at b0 (n of them) as bfloat16 0.0 / 1.0:
+// feature k = raw_bits * packet + bit; bit b is bit 7-(b%8) of header byte b/8; zero past K and past the flow
+static __device__ __forceinline__ uint4 raw_chunk_at(const LayerArgs& a, uint32_t b0, uint32_t n, uint32_t k)
+{
+    if (k >= a.K) return make_uint4(0, 0, 0, 0);
+    uint16_t v[8];
+    if ((a.raw_bits & 7u) == 0 && k + 8u <= a.K) {
+        // the 8 features are the 8 bits of one header byte (k is a multiple of 8): one word load
+        const uint32_t j = k / a.raw_bits, b = k - j * a.raw_bits, byte_i = b >> 3;
+        uint32_t byte = 0;
+        if (j < n) byte = (a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)] >> (8u * (byte_i & 3u))) & 0xFFu;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = ((byte >> (7 - q)) & 1u) ? (uint16_t)0x3F80 : (uint16_t)0;
+        return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t kk = k + q;
+        uint16_t bit = 0;
+        if (kk < a.K) {
+            const uint32_t j = kk / a.raw_bits, b = kk - j * a.raw_bits;
+            if (j < n) {
+                const uint32_t byte_i = b >> 3;
+                const uint32_t word = a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)];
+                const uint32_t byte = (word >> (8u * (byte_i & 3u))) & 0xFFu;
+                bit = (uint16_t)((byte >> (7u - (b & 7u))) & 1u);
+            }
+        }
+        v[q] = bit ? (uint16_t)0x3F80 : (uint16_t)0; // bfloat16 1.0 or 0.0
+    }
+    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+}
+
 // 8 consecutive K values [k, k+8) of escalated row e as bfloat16, zero past K.
 template <int AMODE>
 static __device__ __forceinline__ uint4 load_a_chunk(const LayerArgs& a, bool row_ok, uint32_t row_in_chunk,
@@ -98,37 +141,10 @@ static __device__ __forceinline__ uint4 load_a_chunk(const LayerArgs& a, bool ro
         }
         return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
     }
-    // A_RAW: feature k = raw_bits * packet + bit; bit b is bit 7-(b%8) of header byte b/8
-    uint32_t b0 = a.off[flow], e0 = a.off[flow + 1];
-    b0 = b0 < a.n_pkts ? b0 : a.n_pkts;
-    e0 = e0 < a.n_pkts ? e0 : a.n_pkts;
-    const uint32_t n = e0 > b0 ? e0 - b0 : 0;
-    uint16_t v[8];
-    if ((a.raw_bits & 7u) == 0 && k + 8u <= a.K) {
-        // the 8 features are the 8 bits of one header byte (k is a multiple of 8): one word load
-        const uint32_t j = k / a.raw_bits, b = k - j * a.raw_bits, byte_i = b >> 3;
-        uint32_t byte = 0;
-        if (j < n) byte = (a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)] >> (8u * (byte_i & 3u))) & 0xFFu;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = ((byte >> (7 - q)) & 1u) ? (uint16_t)0x3F80 : (uint16_t)0;
-        return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const uint32_t kk = k + q;
-        uint16_t bit = 0;
-        if (kk < a.K) {
-            const uint32_t j = kk / a.raw_bits, b = kk - j * a.raw_bits;
-            if (j < n) {
-                const uint32_t byte_i = b >> 3;
-                const uint32_t word = a.hdr[(size_t)(b0 + j) * a.hdr_words + (byte_i >> 2)];
-                const uint32_t byte = (word >> (8u * (byte_i & 3u))) & 0xFFu;
-                bit = (uint16_t)((byte >> (7u - (b & 7u))) & 1u);
-            }
-        }
-        v[q] = bit ? (uint16_t)0x3F80 : (uint16_t)0; // bfloat16 1.0 or 0.0
-    }
-    return make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+    // A_RAW
+    uint32_t b0, n;
+    raw_flow_range(a, flow, b0, n);
+    return raw_chunk_at(a, b0, n, k);
 }
 
 static __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u)

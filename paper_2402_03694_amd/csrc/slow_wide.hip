@@ -88,12 +88,27 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
     // two 16-byte chunks of the slab per thread: rows r, 8 k-values each
     const uint32_t cr[2] = {tid / (WSLAB / 8), (tid + WWAVES * 64) / (WSLAB / 8)};
     const uint32_t ck = (tid % (WSLAB / 8)) * 8u;
-    uint4 ra[2];
-    for (uint32_t sl = 0; sl < (resident ? n_slabs : 1u); ++sl) {
+    // raw-bit input: where the two rows' flows start and how many packets they have, once (not per slab)
+    uint32_t raw_b0[2] = {0u, 0u}, raw_n[2] = {0u, 0u};
+    if (AMODE == A_RAW) {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-            ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u], AMODE != A_BF16 ? s_flow[cr[u]] : 0u,
-                                        sl * WSLAB + ck);
+            if (row0 + cr[u] < total) raw_flow_range(a, s_flow[cr[u]], raw_b0[u], raw_n[u]); // (no packets: the row reads as zeros)
+    }
+    // slab sl of the A operand as this thread's two chunks
+    auto fetch = [&](uint32_t sl, uint4 (&r)[2]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (AMODE == A_RAW)
+                r[u] = raw_chunk_at(a, raw_b0[u], raw_n[u], sl * WSLAB + ck);
+            else
+                r[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u], AMODE != A_BF16 ? s_flow[cr[u]] : 0u,
+                                           sl * WSLAB + ck);
+        }
+    };
+    uint4 ra[2];
+    for (uint32_t sl = 0; sl < (resident ? n_slabs : 1u); ++sl) {
+        fetch(sl, ra);
 #pragma unroll
         for (int u = 0; u < 2; ++u) *reinterpret_cast<uint4*>(slab + (sl & 1u) * (WBM * WLDS) + cr[u] * WLDS + ck) = ra[u];
     }
@@ -149,12 +164,7 @@ __global__ __launch_bounds__(WWAVES * 64) void mlp_wide_layer(LayerArgs a, const
 
         for (uint32_t sl = 0; sl < n_slabs; ++sl) {
             const bool more = sl + 1 < n_slabs;
-            if (more && !resident) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u)
-                    ra[u] = load_a_chunk<AMODE>(a, row0 + cr[u] < total, blockIdx.x * WBM + cr[u],
-                                                AMODE != A_BF16 ? s_flow[cr[u]] : 0u, (sl + 1) * WSLAB + ck);
-            }
+            if (more && !resident) fetch(sl + 1, ra);
             const uint4* src[WNI]; // this slab's refills: the next slab of the column block, or the next block's first
 #pragma unroll
             for (int j = 0; j < WNI; ++j) src[j] = more ? wl[j] + (size_t)(sl + 1) * WRING * 64u : nwl[j];
