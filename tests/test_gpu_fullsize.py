@@ -326,6 +326,25 @@ def test_header_bit_workload_full_size():
     kept[o_esc] = False
     assert np.array_equal(g_lab[kept], o_pred[kept])
 
+    # the same workload through sf_classify (features, forest and score in one kernel, one lane per flow; no
+    # feature matrix at all): the oracle's integers on every flow, the same sample of logits
+    pred2 = torch.full((n,), -1, dtype=torch.int16, device=dev)
+    top2 = torch.full((n,), -1, dtype=torch.int16, device=dev)
+    idx2 = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    cnt2 = torch.zeros(1, dtype=torch.int32, device=dev)
+    lab2 = torch.full((n,), -1, dtype=torch.int16, device=dev)
+    log2 = torch.full((n, cfg.n_classes), float("nan"), dtype=torch.float32, device=dev)
+    ctx.sf_classify(d_pk, cfg.depths, d_forest, vmin, d_mlp, None, pred2, top2, idx2, cnt2, lab2, logits=log2,
+                    raw_pkts=cfg.raw_pkts, raw_bits=cfg.raw_bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(pred2.cpu().numpy().view(np.uint16), o_pred)
+    assert np.array_equal(top2.cpu().numpy().view(np.uint16), o_top)
+    assert int(cnt2.cpu().numpy().view(np.uint32)[0]) == cnt
+    assert np.array_equal(idx2.cpu().numpy().view(np.uint32)[:cnt], o_esc)
+    g_lab2 = lab2.cpu().numpy().view(np.uint16)
+    _check_logits(log2.cpu().numpy()[rows], g_lab2, o_logits, o_lab, sub)
+    assert np.array_equal(g_lab2[kept], o_pred[kept])
+
 
 def test_three_tier_full_size():
     """The cascade at 1,048,576 flows in the launch configuration bench.py times: the tree writes the label
